@@ -1,0 +1,130 @@
+#!/usr/bin/env python3
+"""Benchmark of the Triangle Block SYRK on one MI355X.
+
+One step = one call of tbs_syrk_lower on the benchmark workload (N = 4096, M = 4096, fp64,
+C <- C - A A^T on the lower triangle), inputs resident in HBM.  Prints one JSON line with the
+whole-job throughput (N(N+1)M flops per step), the roofline figures of the SYRK kernel (HIP events
+around every launch on the launch stream) and the CPU oracle timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--square] [--no-cpu]
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}       # MI355X dense matrix peaks, TFLOP/s
+# HBM bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel
+# of known size); filled in from the summaries under profiles/ for the workloads measured there.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="syrk_n4096_m4096_f64")
+    ap.add_argument("--square", action="store_true", help="time the square-block baseline instead")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2202_10217_amd import binding as tb
+    from paper_2202_10217_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    tb.load()                                    # fails loudly when the HIP library is missing
+
+    op, A, C0, alpha, beta = inputs.make_config(args.workload)
+    if op != "syrk":
+        print("bench.py: the benchmark step is the SYRK path", file=sys.stderr)
+        return 2
+    N, M = A.shape
+    dname = "f64" if A.dtype == np.float64 else "f32"
+    dA = torch.from_numpy(A).cuda()
+    dC = torch.from_numpy(C0).cuda()
+    fn = tb.tbs_syrk_lower_square if args.square else tb.tbs_syrk_lower
+    flops = float(N) * float(N + 1) * float(M)
+
+    for _ in range(args.warmup):
+        fn(dA, dC, alpha, beta)
+    torch.cuda.synchronize()
+
+    # the timed region: exactly K steps, wall clock, bracketed by synchronisation; each launch is
+    # also bracketed by events on the launch stream (torch's current stream is the one passed down)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        starts[s].record()
+        fn(dA, dC, alpha, beta)
+        ends[s].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(starts, ends)]))
+
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+    info = tb.tbs_syrk_lower_query(tb.TBS_F64 if dname == "f64" else tb.TBS_F32, N, M, args.square)
+    es = 8 if dname == "f64" else 4
+    out = {
+        "metric": "SYRK fp64 TFLOP/s (N^2 M flops)" if dname == "f64" else "SYRK fp32 TFLOP/s (N^2 M flops)",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": dname,
+        "data": "synthetic",
+        "config": {"workload": args.workload, "N": N, "M": M, "alpha": alpha, "beta": beta,
+                   "schedule": "square-blocks" if args.square else "triangle-blocks",
+                   "k": info["k"], "b": info["b"], "c": info["c"], "l": info["l"],
+                   "workgroups": info["n_items"]},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dname],
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS[dname], 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.square)),
+                     "kernel": "tbs_syrk_kernel", "kernel_ms": round(kern_ms, 4),
+                     "flops_per_launch": flops},
+        "io_model": {"S_C_elems": info["S_C_elems"], "S_res_elems": info["S_res_elems"],
+                     "A_bytes_plan": info["A_elems"] * es, "C_bytes_read": info["C_elems"] * es * (beta != 0),
+                     "C_bytes_written": info["C_elems"] * es,
+                     "tbs_bound_bytes": info["tbs_bound_elems"] * es,
+                     "tiled_tbs_lead_bytes": info["tiled_lead_elems"] * es,
+                     "square_equal_area_bytes": info["square_elems"] * es},
+    }
+
+    if not args.no_cpu:
+        import oracle
+        # the oracle as it stands (plain loops, OpenMP over rows), on a bounded sample of the same
+        # workload: the first n rows of A and the leading n x n block of C, all M columns
+        n = min(N, 4096)
+        As = np.ascontiguousarray(A[:n]).astype(np.float64)
+        Cs = np.ascontiguousarray(C0[:n, :n]).astype(np.float64)
+        t0 = time.perf_counter()
+        oracle.syrk_lower(As, Cs, alpha, beta, extended=False)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(float(n) * (n + 1) * M / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"rows 0..{n - 1} of the workload (n={n}, M={M}), 1 repetition, "
+                                         f"{dt:.2f} s"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

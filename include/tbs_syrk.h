@@ -1,0 +1,135 @@
+/*
+ * tbs_syrk.h -- C ABI of the Triangle Block SYRK / Large Block Cholesky library for MI355X.
+ *
+ * The operations are the two kernels of the paper "I/O-Optimal Algorithms for Symmetric Linear
+ * Algebra Kernels" (Section 3, Algorithms 1 and 2), scheduled as its Section 5 prescribes:
+ *   - tbs_syrk_lower       the symmetric rank-k update under the tiled Triangle Block Scheme
+ *                          (Section 5.1, Algorithm 4, tiled form of Section 5.1.4);
+ *   - tbs_syrk_lower_square the same update with square blocks only (the OOC_SYRK scheme the
+ *                          paper compares with, Sections 5 and 5.1.3): the baseline;
+ *   - tbs_potrf_lower      Large Block Cholesky (Section 5.2, Algorithm 5): panel factorisation,
+ *                          triangular solve, Triangle Block trailing update.
+ *
+ * Conventions common to every call
+ *   - All matrices are row-major with a leading dimension counted in elements.
+ *   - Matrix pointers are DEVICE pointers; the caller owns them (and the stream) before, during
+ *     and after the call.  The library allocates and frees no device memory.
+ *   - Only entries on or below the diagonal (column <= row) of a symmetric / triangular matrix
+ *     are read or written; everything above the diagonal is left bit-for-bit untouched.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) unless stated otherwise.
+ *   - Arguments are validated on the host before anything is launched.  Errors are return codes;
+ *     nothing is thrown or aborted.  On an error nothing has been launched.
+ *   - Functions whose names end in _query, _workspace, _enumerate or _string touch no GPU.
+ */
+#ifndef TBS_SYRK_H
+#define TBS_SYRK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { TBS_F64 = 0, TBS_F32 = 1 } tbs_dtype;
+
+typedef enum {
+    TBS_OK = 0,
+    TBS_EINVAL = 1,      /* bad size, leading dimension, dtype or NULL pointer                  */
+    TBS_EWORKSPACE = 2,  /* workspace smaller than the _workspace call asks for                 */
+    TBS_ENOTSPD = 3,     /* potrf met a pivot that is not > 0 (see info_host)                    */
+    TBS_EHIP = 4         /* a HIP runtime call failed (launch error, no device)                  */
+} tbs_status;
+
+/* Plain-text name of a status code; never NULL. */
+const char* tbs_status_string(tbs_status s);
+
+/* ------------------------------------------------------------------------------------------------
+ * SYRK, lower triangle (Algorithm 1 with scaling factors):
+ *     C[i][j] <- beta * C[i][j] + alpha * sum_{k<M} A[i][k] * A[j][k]      for 0 <= j <= i < N.
+ * The paper's update is alpha = beta = 1; the trailing update of Algorithm 5 is alpha = -1.
+ * beta == 0 means C is write-only (old contents, NaN included, are not read).
+ *   A   device, N x M, lda >= max(M,1), never written
+ *   C   device, N x N, ldc >= max(N,1)
+ *   N, M >= 0; N == 0 is a no-op; M == 0 scales the lower triangle by beta.
+ *   workspace / workspace_bytes: device scratch of at least tbs_syrk_lower_workspace() bytes
+ *   (currently 0: NULL is accepted when 0 bytes are required).
+ * The schedule (Section 5.1.4): C is cut into b x b tiles (b = 64); the tile rows are grouped
+ * into triangle blocks R^{i,j} = { u*c + f^{i,j}(u) } of k tile rows (cyclic indexing family,
+ * Section 5.1.2); one workgroup holds the k(k-1)/2 tiles of TB(R) in registers, streams the k
+ * row panels of A through LDS once and uses every staged panel as left and as right operand.
+ * Diagonal zones recurse, the last l tile rows and the recursion base use rectangular blocks,
+ * diagonal tiles have their own code path that computes no tile above the diagonal.
+ * ---------------------------------------------------------------------------------------------- */
+tbs_status tbs_syrk_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_t* bytes);
+
+tbs_status tbs_syrk_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha,
+                          const void* A, int64_t lda, double beta, void* C, int64_t ldc,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Same contract and arguments; every block is a rectangle of tiles (no triangle blocks). */
+tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double alpha,
+                                 const void* A, int64_t lda, double beta, void* C, int64_t ldc,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * The plan the library uses for a given size, for tests and benchmarks (host only).
+ * Element counts follow the paper's accounting (Sections 5.1.3, 5.1.4): A elements loaded by
+ * every block (k*b*M per triangle block), C elements loaded once.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t k;                 /* side of a triangle block, in tile rows                         */
+    int32_t b;                 /* tile side, in elements                                         */
+    int32_t c;                 /* top-level modulus of the cyclic family (0: no triangle blocks) */
+    int32_t l;                 /* top-level leftover tile rows, T - k*c                          */
+    int32_t levels;            /* recursion levels that use triangle blocks                      */
+    int32_t tile_rows;         /* T = ceil(N / b)                                                */
+    int64_t n_items;           /* workgroups launched                                            */
+    int64_t n_tri_blocks;      /* triangle blocks, all levels                                    */
+    int64_t n_rect_blocks;     /* rectangular blocks (leftover rows, recursion base)             */
+    int64_t n_diag_tiles;      /* diagonal tiles                                                 */
+    int64_t S_C_elems;         /* b^2 k(k-1)/2: C elements resident per triangle block           */
+    int64_t S_res_elems;       /* S_C plus the LDS staging buffers of A                          */
+    double  A_elems;           /* A elements this plan loads (all blocks, all levels)            */
+    double  A_elems_top;       /* of which top-level triangle blocks: Q1 = c^2 k b M             */
+    double  C_elems;           /* N(N+1)/2                                                       */
+    double  tbs_bound_elems;   /* N^2 M / (sqrt(2) sqrt(S_C))  (corollary of Section 4.1)        */
+    double  tiled_lead_elems;  /* N^2 M / ((k-1) b)            (Section 5.1.4)                   */
+    double  square_elems;      /* N^2 M / sqrt(S_C)            (square blocks of equal area)     */
+} tbs_plan_info;
+
+/* square != 0 describes the plan of tbs_syrk_lower_square. */
+tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t square,
+                                tbs_plan_info* out);
+
+/* Expands the plan into its work list, with the very index arithmetic the kernels use.
+ * Item t occupies rows[t*8 .. t*8+7]:  [0] kind (0 triangle block, 1 rectangle, 2 diagonal tile),
+ * [1] number of row-side tile rows, [2] number of column-side tile rows, [3..7] tile-row ids
+ * (triangle block: the k members of R in zone order; rectangle: column-side ids first, then the
+ * row-side ids; unused slots are -1).  A rectangle updates the tiles (r, q) of its row x column
+ * product with q < r only.  `capacity` counts items; *n_items receives the number the plan has
+ * (call with items == NULL to size the buffer).  HOST pointers. */
+tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int32_t square,
+                                    int32_t* items, int64_t capacity, int64_t* n_items);
+
+/* ------------------------------------------------------------------------------------------------
+ * Cholesky, lower triangle, in place (Algorithm 2; schedule: Algorithm 5, Large Block Cholesky):
+ * the lower triangle of the symmetric positive definite matrix A (device, N x N, lda >=
+ * max(N,1)) is replaced by L with L * L^T = A.
+ *   workspace: device scratch of at least tbs_potrf_lower_workspace() bytes.
+ *   info_host: HOST pointer or NULL.  If not NULL the call synchronises the stream before it
+ *   returns and stores 0, or the 1-based index of the first pivot that is not > 0 (the return
+ *   value is then TBS_ENOTSPD and the contents of A are unspecified).  With NULL the call is
+ *   asynchronous and a failed pivot goes unreported.
+ * ---------------------------------------------------------------------------------------------- */
+tbs_status tbs_potrf_lower_workspace(tbs_dtype dtype, int64_t N, size_t* bytes);
+
+tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda,
+                           void* workspace, size_t workspace_bytes,
+                           int32_t* info_host, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TBS_SYRK_H */

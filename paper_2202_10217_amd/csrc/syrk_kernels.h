@@ -1,0 +1,22 @@
+// syrk_kernels.h -- launch interface of the Triangle Block SYRK kernels (device code in the .hip).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "tbs_plan.h"
+
+namespace tbs {
+
+// C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`; one workgroup per block.
+// All pointers are device pointers; sizes have been validated by the caller.
+hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
+                       int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream);
+
+// C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, all row-major device matrices.  C may alias
+// R when n <= 192 and every workgroup's rows of R are only its own rows of C (the in-place
+// triangular solve by an inverted diagonal block): a workgroup reads all it needs before it writes.
+hipError_t launch_gemm_nt(bool f32, int64_t m, int64_t n, int64_t K, double alpha, const void* R,
+                          int64_t ldr, const void* Q, int64_t ldq, double beta, void* C, int64_t ldc,
+                          hipStream_t stream);
+
+}  // namespace tbs

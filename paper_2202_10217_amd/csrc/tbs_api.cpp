@@ -1,0 +1,290 @@
+// tbs_api.cpp -- the C ABI declared in include/tbs_syrk.h: argument checks, plan cache, launches,
+// and the Large Block Cholesky driver (Algorithm 5 of the paper) built from the kernels.
+#include "tbs_syrk.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <map>
+#include <mutex>
+#include <utility>
+
+#include "potrf_kernels.h"
+#include "syrk_kernels.h"
+#include "tbs_planner.h"
+
+namespace {
+
+using tbs::kK;
+using tbs::kTile;
+
+constexpr int64_t kMaxN = (int64_t)kTile << 15;       // descriptor limit: 2^15 tile rows
+constexpr int64_t kMaxM = (int64_t)1 << 30;
+
+bool dtype_ok(tbs_dtype d) { return d == TBS_F64 || d == TBS_F32; }
+size_t elem_size(tbs_dtype d) { return d == TBS_F32 ? 4 : 8; }
+
+// Plans depend on the number of tile rows only; they are built once and kept.
+const tbs::Plan* cached_plan(int32_t T, bool square)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int32_t, bool>, tbs::Plan> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    auto key = std::make_pair(T, square);
+    auto it = cache.find(key);
+    if (it == cache.end()) {
+        tbs::Plan p;
+        if (!tbs::build_plan(T, square, &p)) return nullptr;
+        it = cache.emplace(key, p).first;
+    }
+    return &it->second;
+}
+
+tbs_status check_syrk(tbs_dtype dtype, int64_t N, int64_t M, const void* A, int64_t lda, const void* C,
+                      int64_t ldc)
+{
+    if (!dtype_ok(dtype)) return TBS_EINVAL;
+    if (N < 0 || M < 0 || N > kMaxN || M > kMaxM) return TBS_EINVAL;
+    if (lda < (M > 1 ? M : 1) || ldc < (N > 1 ? N : 1)) return TBS_EINVAL;
+    if (N > 0 && M > 0 && A == nullptr) return TBS_EINVAL;
+    if (N > 0 && C == nullptr) return TBS_EINVAL;
+    return TBS_OK;
+}
+
+tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,
+                     int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream)
+{
+    if (N == 0) return TBS_OK;
+    const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    const tbs::Plan* plan = cached_plan(T, square);
+    if (!plan) return TBS_EINVAL;
+    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, stream);
+    return e == hipSuccess ? TBS_OK : TBS_EHIP;
+}
+
+// ---- Large Block Cholesky ------------------------------------------------------------------------
+constexpr size_t kInfoBytes = 256;                     // info word, padded to keep the rest aligned
+
+struct Lbc {
+    tbs_dtype dtype;
+    size_t es;
+    char* A;
+    int64_t lda;
+    char* linv;          // one 64 x 64 inverse per diagonal tile
+    int32_t* info;
+    hipStream_t stream;
+    int64_t big_block;   // panel width at the top level
+    hipError_t err = hipSuccess;
+
+    char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
+    char* inv_of(int64_t row) const { return linv + (size_t)(row / kTile) * kTile * kTile * es; }
+    void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+
+    int64_t block_for(int64_t n) const
+    {
+        if (n >= 4 * big_block) return big_block;
+        if (n > 1024) return 256;
+        if (n > 256) return 128;
+        return kTile;
+    }
+
+    // X = A[row0 : row0+m, col0 : col0+nb]  <-  X * L^{-T},  L = A[col0 : col0+nb, col0 : col0+nb]
+    // (the solve of Algorithm 5, "TRSM"): recursive on the column blocks of L; a 64-wide block is
+    // solved by multiplying with the inverse of its diagonal tile.
+    void trsm(int64_t row0, int64_t m, int64_t col0, int64_t nb)
+    {
+        if (m <= 0 || nb <= 0) return;
+        const bool f32 = dtype == TBS_F32;
+        if (nb <= kTile) {
+            note(tbs::launch_gemm_nt(f32, m, nb, nb, 1.0, at(row0, col0), lda, inv_of(col0), kTile, 0.0,
+                                     at(row0, col0), lda, stream));
+            return;
+        }
+        const int64_t nb1 = ((nb / kTile + 1) / 2) * kTile;
+        trsm(row0, m, col0, nb1);
+        note(tbs::launch_gemm_nt(f32, m, nb - nb1, nb1, -1.0, at(row0, col0), lda, at(col0 + nb1, col0), lda,
+                                 1.0, at(row0, col0 + nb1), lda, stream));
+        trsm(row0, m, col0 + nb1, nb - nb1);
+    }
+
+    // Algorithm 5 on A[off : off+n, off : off+n]; the one-tile Cholesky of the panel is the same
+    // routine with a smaller block (the recursive variant the paper mentions in Section 5.2.1).
+    void potrf(int64_t off, int64_t n)
+    {
+        if (n <= 0) return;
+        if (n <= kTile) {
+            note(tbs::launch_potrf_tile(dtype == TBS_F32, (int)n, at(off, off), lda, inv_of(off), info,
+                                        (int32_t)off, stream));
+            return;
+        }
+        const int64_t B = block_for(n);
+        for (int64_t p0 = 0; p0 < n; p0 += B) {
+            const int64_t nb = (B < n - p0) ? B : n - p0;
+            potrf(off + p0, nb);                                        // A[I0,I0] <- CHOL
+            const int64_t rest = n - p0 - nb, row0 = off + p0 + nb;
+            if (rest <= 0) continue;
+            trsm(row0, rest, off + p0, nb);                             // A[I1,I0] <- TRSM
+            const tbs_status st = syrk_impl(false, dtype, rest, nb, -1.0, at(row0, off + p0), lda, 1.0,
+                                            at(row0, row0), lda, stream);  // A[I1,I1] <- TBS
+            if (st != TBS_OK) note(hipErrorUnknown);
+        }
+    }
+};
+
+int64_t default_big_block()
+{
+    const char* e = std::getenv("TBS_POTRF_BLOCK");
+    if (e) {
+        const long v = std::atol(e);
+        if (v >= kTile && v <= 4096 && v % kTile == 0) return v;
+    }
+    return 512;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tbs_status_string(tbs_status s)
+{
+    switch (s) {
+        case TBS_OK: return "ok";
+        case TBS_EINVAL: return "invalid argument";
+        case TBS_EWORKSPACE: return "workspace too small";
+        case TBS_ENOTSPD: return "matrix is not positive definite";
+        case TBS_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+tbs_status tbs_syrk_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_t* bytes)
+{
+    if (!dtype_ok(dtype) || N < 0 || M < 0 || N > kMaxN || M > kMaxM || !bytes) return TBS_EINVAL;
+    *bytes = 0;
+    return TBS_OK;
+}
+
+tbs_status tbs_syrk_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A, int64_t lda,
+                          double beta, void* C, int64_t ldc, void* workspace, size_t workspace_bytes,
+                          void* hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    const tbs_status st = check_syrk(dtype, N, M, A, lda, C, ldc);
+    if (st != TBS_OK) return st;
+    return syrk_impl(false, dtype, N, M, alpha, A, lda, beta, C, ldc, (hipStream_t)hip_stream);
+}
+
+tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,
+                                 int64_t lda, double beta, void* C, int64_t ldc, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    const tbs_status st = check_syrk(dtype, N, M, A, lda, C, ldc);
+    if (st != TBS_OK) return st;
+    return syrk_impl(true, dtype, N, M, alpha, A, lda, beta, C, ldc, (hipStream_t)hip_stream);
+}
+
+tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t square, tbs_plan_info* out)
+{
+    if (!dtype_ok(dtype) || N < 0 || M < 0 || N > kMaxN || M > kMaxM || !out) return TBS_EINVAL;
+    const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    const tbs::Plan* plan = cached_plan(T, square != 0);
+    if (!plan) return TBS_EINVAL;
+    tbs::PlanStats st;
+    tbs::plan_stats(*plan, N, M, &st);
+    tbs_plan_info r{};
+    r.k = kK;
+    r.b = kTile;
+    r.levels = st.levels;
+    r.c = st.levels > 0 ? plan->c[0] : 0;
+    r.l = st.levels > 0 ? T - kK * plan->c[0] : T;
+    r.tile_rows = T;
+    r.n_items = plan->n_items;
+    r.n_tri_blocks = st.n_tri;
+    r.n_rect_blocks = st.n_rect;
+    r.n_diag_tiles = st.n_diag;
+    r.S_C_elems = (int64_t)kTile * kTile * kK * (kK - 1) / 2;
+    const int64_t kc = dtype == TBS_F32 ? 32 : 16;      // staged columns per chunk, two buffers
+    r.S_res_elems = r.S_C_elems + 2 * (int64_t)kK * kTile * kc;
+    r.A_elems = st.A_elems;
+    r.A_elems_top = st.A_elems_top;
+    r.C_elems = st.C_elems;
+    const double n2m = (double)N * (double)N * (double)M;
+    r.tbs_bound_elems = n2m / (std::sqrt(2.0) * std::sqrt((double)r.S_C_elems));
+    r.tiled_lead_elems = n2m / ((kK - 1.0) * kTile);
+    r.square_elems = n2m / std::sqrt((double)r.S_C_elems);
+    *out = r;
+    return TBS_OK;
+}
+
+tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int32_t square, int32_t* items,
+                                    int64_t capacity, int64_t* n_items)
+{
+    if (!dtype_ok(dtype) || N < 0 || N > kMaxN || !n_items) return TBS_EINVAL;
+    const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    const tbs::Plan* plan = cached_plan(T, square != 0);
+    if (!plan) return TBS_EINVAL;
+    *n_items = plan->n_items;
+    if (!items) return TBS_OK;
+    if (capacity < plan->n_items) return TBS_EWORKSPACE;
+    for (int32_t t = 0; t < plan->n_items; ++t) {
+        tbs::Item it;
+        tbs::tbs_decode(*plan, t, it);
+        int32_t* o = items + (int64_t)t * 8;
+        o[0] = it.kind;
+        o[1] = it.nrow;
+        o[2] = it.ncol;
+        for (int s = 0; s < 5; ++s) o[3 + s] = it.rows[s];
+    }
+    return TBS_OK;
+}
+
+tbs_status tbs_potrf_lower_workspace(tbs_dtype dtype, int64_t N, size_t* bytes)
+{
+    if (!dtype_ok(dtype) || N < 0 || N > kMaxN || !bytes) return TBS_EINVAL;
+    const size_t T = (size_t)((N + kTile - 1) / kTile);
+    *bytes = kInfoBytes + T * kTile * kTile * elem_size(dtype);
+    return TBS_OK;
+}
+
+tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, void* workspace,
+                           size_t workspace_bytes, int32_t* info_host, void* hip_stream)
+{
+    size_t need = 0;
+    if (tbs_potrf_lower_workspace(dtype, N, &need) != TBS_OK) return TBS_EINVAL;
+    if (lda < (N > 1 ? N : 1)) return TBS_EINVAL;
+    if (N > 0 && A == nullptr) return TBS_EINVAL;
+    if (N == 0) {
+        if (info_host) *info_host = 0;
+        return TBS_OK;
+    }
+    if (workspace == nullptr || workspace_bytes < need) return TBS_EWORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 15) != 0) return TBS_EINVAL;
+
+    Lbc ctx;
+    ctx.dtype = dtype;
+    ctx.es = elem_size(dtype);
+    ctx.A = static_cast<char*>(A);
+    ctx.lda = lda;
+    ctx.info = static_cast<int32_t*>(workspace);
+    ctx.linv = static_cast<char*>(workspace) + kInfoBytes;
+    ctx.stream = (hipStream_t)hip_stream;
+    ctx.big_block = default_big_block();
+    ctx.note(tbs::launch_fill_i32(ctx.info, 0, 1, ctx.stream));
+    ctx.potrf(0, N);
+    if (ctx.err != hipSuccess) return TBS_EHIP;
+    if (info_host) {
+        int32_t info = 0;
+        if (hipMemcpyAsync(&info, ctx.info, sizeof(info), hipMemcpyDeviceToHost, ctx.stream) != hipSuccess)
+            return TBS_EHIP;
+        if (hipStreamSynchronize(ctx.stream) != hipSuccess) return TBS_EHIP;
+        *info_host = info;
+        if (info != 0) return TBS_ENOTSPD;
+    }
+    return TBS_OK;
+}
+
+}  // extern "C"

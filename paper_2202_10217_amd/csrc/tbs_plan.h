@@ -1,0 +1,141 @@
+// tbs_plan.h -- the Triangle Block Scheme work list as a compact descriptor plus index arithmetic.
+//
+// The partition of C follows Algorithm 4 / Section 5.1.4 of the paper, on b x b tiles:
+//   level 0 is the whole matrix (T tile rows); a level with T_L tile rows per zone picks
+//   c_L = largest integer <= T_L / k coprime with every integer of [2, k-2] (Section 5.1.2);
+//   if c_L >= k-1 its c_L^2 triangle blocks R^{i,j} = { u c_L + f^{i,j}(u) : u < k }, with the
+//   cyclic family f(0) = j, f(u) = (i + j (u-1)) mod c_L, cover the k(k-1)/2 square zones,
+//   the l_L = T_L - k c_L last tile rows are covered by rectangular blocks, and each of the k
+//   diagonal zones (c_L tile rows) becomes a zone of level L+1;  if c_L < k-1 the zone is a base
+//   zone: one triangle block on its consecutive rows when it has at most k of them, rectangular
+//   blocks otherwise.  Diagonal tiles are never part of a block: they form one list of their own.
+//
+// The descriptor is small enough to be a kernel argument; every workgroup turns its index into
+// its block with tbs_decode().  The host uses the same function to expand, count and check plans,
+// so what is tested on the CPU is what the kernels execute.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define TBS_HD __host__ __device__ inline
+#else
+#define TBS_HD inline
+#endif
+
+namespace tbs {
+
+constexpr int kTile = 64;        // b: tile side in elements
+constexpr int kK = 4;            // k: tile rows per triangle block
+constexpr int kMaxLevels = 10;
+constexpr int kMaxSegs = 28;
+constexpr int kRectRows = 2;     // rectangular block: at most 2 x 3 tiles
+constexpr int kRectCols = 3;
+constexpr int kMaxPanels = 5;    // panels of A a block can stage (k, or kRectRows + kRectCols)
+
+enum ItemKind : int32_t { kTri = 0, kRect = 1, kDiag = 2, kEmpty = 3 };
+
+enum SegKind : int32_t {
+    kSegTri = 0,       // c^2 triangle blocks in each zone of a level
+    kSegTriBase = 1,   // one triangle block on the consecutive rows of each base zone
+    kSegRect = 2,      // grid of rectangular blocks inside each zone of a level
+    kSegDiag = 3       // all diagonal tiles
+};
+
+struct Seg {
+    int32_t kind;
+    int32_t first;     // index of the first item of the segment
+    int32_t count;     // number of items
+    int32_t level;     // zones of this level are addressed (k^level of them)
+    int32_t r0, r1;    // kSegRect: tile rows [r0, r1) relative to the zone; kSegTriBase: r1 = zone size
+    int32_t c0, c1;    // kSegRect: tile columns [c0, c1) relative to the zone
+    int32_t nI, nJ;    // kSegRect: blocks per zone along rows / columns
+    int32_t mr, nc;    // kSegRect: block shape in tiles
+};
+
+struct Plan {
+    int32_t k;
+    int32_t T;                  // tile rows of the whole matrix
+    int32_t nseg;
+    int32_t n_items;
+    int32_t c[kMaxLevels];      // modulus of each level that has triangle blocks
+    Seg seg[kMaxSegs];
+};
+
+struct Item {
+    int32_t kind;
+    int32_t nrow;               // triangle block: members of R; rectangle: row-side tile rows
+    int32_t ncol;               // rectangle: column-side tile rows; otherwise 0
+    // tile rows, -1 = unused.  Triangle block: R in zone order in slots 0..k-1.  Rectangle: column
+    // side in slots 0..2, row side in slots 3..4.  Diagonal tile: slot 0.
+    int32_t rows[kMaxPanels];
+};
+
+// first tile row of zone z of a level: the zone is reached by choosing digit d_m at level m
+TBS_HD int32_t zone_base(const Plan& p, int32_t level, int32_t z)
+{
+    int32_t base = 0;
+    for (int32_t m = level - 1; m >= 0; --m) {
+        base += (z % kK) * p.c[m];
+        z /= kK;
+    }
+    return base;
+}
+
+TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
+{
+    it.kind = kEmpty;
+    it.nrow = 0;
+    it.ncol = 0;
+    for (int s = 0; s < kMaxPanels; ++s) it.rows[s] = -1;
+    int32_t si = 0;
+    while (si + 1 < p.nseg && id >= p.seg[si + 1].first) ++si;
+    const Seg& sg = p.seg[si];
+    const int32_t t = id - sg.first;
+    if (t < 0 || t >= sg.count) return;
+    if (sg.kind == kSegTri) {
+        const int32_t c = p.c[sg.level];
+        const int32_t z = t / (c * c);
+        const int32_t ij = t - z * c * c;
+        const int32_t i = ij / c, j = ij - i * c;
+        const int32_t base = zone_base(p, sg.level, z);
+        it.kind = kTri;
+        it.nrow = kK;
+        it.rows[0] = base + j;
+        int32_t f = i;                              // f(1) = i, f(u+1) = f(u) + j mod c
+        for (int32_t u = 1; u < kK; ++u) {
+            it.rows[u] = base + u * c + f;
+            f += j;
+            if (f >= c) f -= c;
+        }
+    } else if (sg.kind == kSegTriBase) {
+        const int32_t base = zone_base(p, sg.level, t);
+        it.kind = kTri;
+        it.nrow = sg.r1;
+        for (int32_t u = 0; u < kK; ++u)
+            if (u < sg.r1) it.rows[u] = base + u;
+    } else if (sg.kind == kSegRect) {
+        const int32_t per_zone = sg.nI * sg.nJ;
+        const int32_t z = t / per_zone;
+        const int32_t rem = t - z * per_zone;
+        const int32_t I = rem / sg.nJ, J = rem - I * sg.nJ;
+        const int32_t base = zone_base(p, sg.level, z);
+        const int32_t ra = sg.r0 + I * sg.mr;
+        const int32_t rb = (ra + sg.mr < sg.r1) ? ra + sg.mr : sg.r1;
+        const int32_t ca = sg.c0 + J * sg.nc;
+        const int32_t cb = (ca + sg.nc < sg.c1) ? ca + sg.nc : sg.c1;
+        if (ca >= rb - 1) return;                  // no tile strictly below the diagonal: empty
+        it.kind = kRect;
+        it.ncol = cb - ca;
+        it.nrow = rb - ra;
+        for (int32_t q = 0; q < kRectCols; ++q)
+            if (q < it.ncol) it.rows[q] = base + ca + q;
+        for (int32_t r = 0; r < kRectRows; ++r)
+            if (r < it.nrow) it.rows[kRectCols + r] = base + ra + r;
+    } else {
+        it.kind = kDiag;
+        it.nrow = 1;
+        it.rows[0] = t;
+    }
+}
+
+}  // namespace tbs

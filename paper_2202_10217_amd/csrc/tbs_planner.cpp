@@ -1,0 +1,145 @@
+// tbs_planner.cpp -- builds the work-list descriptor of the tiled Triangle Block Scheme
+// (Algorithm 4 with the changes of Section 5.1.4), flattening its recursion level by level.
+#include "tbs_planner.h"
+
+#include <algorithm>
+#include <numeric>
+#include <vector>
+
+namespace tbs {
+
+int32_t choose_c(int32_t upper, int32_t k)
+{
+    for (int32_t c = upper; c > 0; --c) {
+        bool ok = true;
+        for (int32_t d = 2; d <= k - 2 && ok; ++d) ok = std::gcd(c, d) == 1;
+        if (ok) return c;
+    }
+    return 0;
+}
+
+namespace {
+
+Seg rect_seg(int32_t level, int64_t nz, int32_t r0, int32_t r1, int32_t c0, int32_t c1)
+{
+    Seg s{};
+    s.kind = kSegRect;
+    s.level = level;
+    s.r0 = r0; s.r1 = r1; s.c0 = c0; s.c1 = c1;
+    s.mr = kRectRows; s.nc = kRectCols;
+    s.nI = (r1 - r0 + s.mr - 1) / s.mr;
+    s.nJ = (c1 - c0 + s.nc - 1) / s.nc;
+    s.count = (int32_t)(nz * s.nI * s.nJ);
+    return s;
+}
+
+}  // namespace
+
+bool build_plan(int32_t T, bool square, Plan* out)
+{
+    if (T < 0 || T > (1 << 15)) return false;
+    Plan p{};
+    p.k = kK;
+    p.T = T;
+    std::vector<Seg> tri, rect, base;
+    const int32_t k = p.k;
+    if (square) {
+        if (T >= 2) rect.push_back(rect_seg(0, 1, 0, T, 0, T - 1));
+    } else {
+        int32_t level = 0, Tl = T;
+        int64_t nz = 1;
+        for (;;) {
+            const int32_t c = choose_c(Tl / k, k);
+            const bool room = level < kMaxLevels - 1 &&
+                              (int)(tri.size() + rect.size()) + 3 < kMaxSegs - 2;
+            if (c < k - 1 || !room) {                       // base zones (c too small)
+                if (Tl >= 2) {
+                    if (Tl <= k) {
+                        Seg s{};
+                        s.kind = kSegTriBase;
+                        s.level = level;
+                        s.r1 = Tl;
+                        s.count = (int32_t)nz;
+                        base.push_back(s);
+                    } else {
+                        rect.push_back(rect_seg(level, nz, 0, Tl, 0, Tl - 1));
+                    }
+                }
+                break;
+            }
+            p.c[level] = c;
+            Seg s{};
+            s.kind = kSegTri;
+            s.level = level;
+            s.count = (int32_t)(nz * c * c);
+            tri.push_back(s);
+            const int32_t done = k * c, l = Tl - done;
+            if (l > 0) {                                    // the last l tile rows
+                rect.push_back(rect_seg(level, nz, done, Tl, 0, done));
+                if (l >= 2) rect.push_back(rect_seg(level, nz, done, Tl, done, Tl - 1));
+            }
+            nz *= k;
+            Tl = c;
+            ++level;
+        }
+    }
+    // longest blocks first: triangle blocks by level, rectangles, base triangles, diagonal tiles
+    int32_t n = 0, first = 0;
+    auto push = [&](Seg s) {
+        if (s.count <= 0) return;
+        s.first = first;
+        first += s.count;
+        p.seg[n++] = s;
+    };
+    for (const Seg& s : tri) push(s);
+    for (const Seg& s : rect) push(s);
+    for (const Seg& s : base) push(s);
+    if (T > 0) {
+        Seg d{};
+        d.kind = kSegDiag;
+        d.count = T;
+        push(d);
+    }
+    p.nseg = n;
+    p.n_items = first;
+    *out = p;
+    return true;
+}
+
+void plan_stats(const Plan& p, int64_t N, int64_t M, PlanStats* st)
+{
+    PlanStats r{};
+    for (int32_t s = 0; s < p.nseg; ++s)
+        if (p.seg[s].kind == kSegTri) r.levels = std::max(r.levels, p.seg[s].level + 1);
+    auto panel_rows = [&](int32_t t) -> double {
+        const int64_t lo = (int64_t)t * kTile;
+        return (double)std::max<int64_t>(0, std::min<int64_t>(kTile, N - lo));
+    };
+    for (int32_t s = 0; s < p.nseg; ++s) {
+        const Seg& sg = p.seg[s];
+        for (int32_t t = 0; t < sg.count; ++t) {
+            Item it;
+            tbs_decode(p, sg.first + t, it);
+            double a = 0;
+            if (it.kind == kTri) {
+                ++r.n_tri;
+                for (int32_t u = 0; u < it.nrow; ++u) a += panel_rows(it.rows[u]);
+            } else if (it.kind == kRect) {
+                ++r.n_rect;
+                for (int32_t u = 0; u < kMaxPanels; ++u)
+                    if (it.rows[u] >= 0) a += panel_rows(it.rows[u]);
+            } else if (it.kind == kDiag) {
+                ++r.n_diag;
+                a += panel_rows(it.rows[0]);
+            } else {
+                ++r.n_empty;
+            }
+            r.A_elems += a * (double)M;
+            if (sg.kind == kSegTri && sg.level == 0) r.A_elems_top += a * (double)M;
+        }
+    }
+    r.C_elems = 0.5 * (double)N * (double)(N + 1);
+    *st = r;
+}
+
+}  // namespace tbs
