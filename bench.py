@@ -27,6 +27,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="syrk_n4096_m4096_f64")
+    ap.add_argument("--shape", default=None, help="N,M,dtype: a SYRK shape outside the configuration list "
+                    "(C <- C - A A^T, A iid N(0,1)/sqrt(M)), for kernel studies")
     ap.add_argument("--square", action="store_true", help="time the square-block baseline instead")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
@@ -44,7 +46,15 @@ def main():
         return 3
     tb.load()                                    # fails loudly when the HIP library is missing
 
-    op, A, C0, alpha, beta = inputs.make_config(args.workload)
+    if args.shape:
+        n_, m_, dt_ = args.shape.split(",")
+        dt_ = np.float64 if dt_ in ("f64", "float64") else np.float32
+        args.workload = f"syrk_n{n_}_m{m_}_{'f64' if dt_ == np.float64 else 'f32'}_custom"
+        op, alpha, beta = "syrk", -1.0, 1.0
+        A = inputs.normal_matrix(int(n_), int(m_), 7, 1.0 / np.sqrt(int(m_)), dt_)
+        C0 = inputs.symmetric_uniform(int(n_), 8, dtype=dt_)
+    else:
+        op, A, C0, alpha, beta = inputs.make_config(args.workload)
     if op != "syrk":
         print("bench.py: the benchmark step is the SYRK path", file=sys.stderr)
         return 2

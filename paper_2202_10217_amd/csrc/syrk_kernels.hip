@@ -78,6 +78,33 @@ struct RectShape {                        // panels 0..2 = column side, 3..4 = r
     static constexpr int slot(int i, int j) { return i * 3 + j; }
 };
 
+// which slots / row-side panels / column-side panels / LDS panels a set of slots needs
+template <class Shape> constexpr bool slot_on(uint32_t slots, int i, int j)
+{
+    return Shape::active(i, j) && ((slots >> Shape::slot(i, j)) & 1u);
+}
+template <class Shape> constexpr bool a_used(uint32_t slots, int i)
+{
+    bool u = false;
+    for (int j = 0; j < Shape::NB; ++j) u = u || slot_on<Shape>(slots, i, j);
+    return u;
+}
+template <class Shape> constexpr bool b_used(uint32_t slots, int j)
+{
+    bool u = false;
+    for (int i = 0; i < Shape::NA; ++i) u = u || slot_on<Shape>(slots, i, j);
+    return u;
+}
+template <class Shape> constexpr uint32_t panels_of(uint32_t slots)
+{
+    uint32_t pm = 0;
+    for (int i = 0; i < Shape::NA; ++i)
+        if (a_used<Shape>(slots, i)) pm |= 1u << Shape::a_panel(i);
+    for (int j = 0; j < Shape::NB; ++j)
+        if (b_used<Shape>(slots, j)) pm |= 1u << Shape::b_panel(j);
+    return pm;
+}
+
 // ---- operands of one launch --------------------------------------------------------------------
 // C[rows, cols] <- beta*C + alpha * R[rows, :] * Q[cols, :]^T.  SYRK has R == Q == A and updates
 // only tiles strictly below the diagonal; the general product (used by the Cholesky driver for its
@@ -93,37 +120,67 @@ struct Mats {
 };
 
 // ---- global -> register -> LDS staging of one chunk --------------------------------------------
-template <typename T, int NP>
+template <typename T>
+__device__ __forceinline__ bool vec_ok(const T* p, int64_t ld)
+{
+    return ((reinterpret_cast<uintptr_t>(p) & 15) == 0) && ((ld * sizeof(T)) % 16 == 0);
+}
+
+// Thread t moves, for every panel, two 16-byte pieces: rows t/8 and t/8 + 32, columns
+// [ (t%8)*VEC, +VEC ) of the chunk: 8 threads cover the 128 contiguous bytes of one row.
+// PANELS (compile time) selects the panels that are staged at all.
+template <typename T, int NP, uint32_t PANELS>
 struct Stager {
     static constexpr int KC = Cfg<T>::KC, LDK = Cfg<T>::LDK, VEC = Cfg<T>::VEC;
     u32x4 reg[2 * NP];
+    const T* base[NP];                     // matrix of each panel (wavefront-uniform)
+    int64_t ld[NP];
+    int64_t off[NP];                       // element offset of the thread's first piece in chunk 0
+    uint32_t valid;                        // bit 2p+h: piece h of panel p exists (inside the matrix)
 
-    // prow[p]: tile row of panel p (-1: absent) in matrix base[p] with nrows[p] rows.
-    __device__ __forceinline__ void load(const T* const (&base)[NP], const int64_t (&ld)[NP],
-                                         const int (&nrows)[NP], const int (&prow)[NP], int M, int k0,
-                                         bool fast, int tid)
+    static constexpr bool on(int p) { return (PANELS >> p) & 1u; }
+
+    // prow[p]: tile row of panel p (-1: absent) in matrix base_[p] with nrows[p] rows.
+    __device__ __forceinline__ void init(const T* const (&base_)[NP], const int64_t (&ld_)[NP],
+                                         const int (&nrows)[NP], const int (&prow)[NP], int tid)
     {
         const int v = tid & 7, r = tid >> 3;
+        valid = 0;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
+            if (!on(p)) continue;
+            base[p] = base_[p];
+            ld[p] = ld_[p];
+            const int grow = prow[p] * kTile + r;
+            off[p] = (int64_t)grow * ld_[p] + v * VEC;
+            if (prow[p] >= 0 && grow < nrows[p]) valid |= 1u << (2 * p);
+            if (prow[p] >= 0 && grow + 32 < nrows[p]) valid |= 2u << (2 * p);
+        }
+    }
+
+    // General case.  whole: the chunk lies inside [0, M) and 16-byte loads are legal; otherwise
+    // elements are fetched one by one and those beyond M read as zero.  Missing rows read as zero.
+    __device__ __forceinline__ void load_checked(int M, int k0, bool whole, int tid)
+    {
+        const int v = tid & 7;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            if (!on(p)) continue;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                u32x4 val = {0u, 0u, 0u, 0u};
-                const int grow = prow[p] * kTile + h * 32 + r;
-                if (prow[p] >= 0 && grow < nrows[p]) {
-                    const T* src = base[p] + (int64_t)grow * ld[p] + k0 + v * VEC;
-                    if (fast) {
-                        val = *reinterpret_cast<const u32x4*>(src);
+                union { u32x4 q4; T e[VEC]; } tmp;
+                tmp.q4 = u32x4{0u, 0u, 0u, 0u};
+                if ((valid >> (2 * p + h)) & 1u) {
+                    const T* src = base[p] + off[p] + (int64_t)h * 32 * ld[p] + k0;
+                    if (whole) {
+                        tmp.q4 = *reinterpret_cast<const u32x4*>(src);
                     } else {
-                        union { u32x4 q; T e[VEC]; } tmp;
-                        tmp.q = val;
 #pragma unroll
                         for (int e = 0; e < VEC; ++e)
                             if (k0 + v * VEC + e < M) tmp.e[e] = src[e];
-                        val = tmp.q;
                     }
                 }
-                reg[p * 2 + h] = val;
+                reg[p * 2 + h] = tmp.q4;
             }
         }
     }
@@ -132,52 +189,72 @@ struct Stager {
     {
         const int v = tid & 7, r = tid >> 3;
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
+        for (int p = 0; p < NP; ++p) {
+            if (!on(p)) continue;
 #pragma unroll
             for (int h = 0; h < 2; ++h)
                 *reinterpret_cast<u32x4*>(&buf[(p * kTile + h * 32 + r) * LDK + v * VEC]) = reg[p * 2 + h];
+        }
     }
 };
 
-template <typename T>
-__device__ __forceinline__ bool vec_ok(const T* p, int64_t ld)
-{
-    return ((reinterpret_cast<uintptr_t>(p) & 15) == 0) && ((ld * sizeof(T)) % 16 == 0);
-}
+// ---- MFMA operands of one k-step (4 columns of the chunk) ---------------------------------------
+// Row side: the four 16-row groups of each row-side panel.  Column side: the wavefront's group of
+// each column-side panel.  Lane l holds element [row l%16][column l/16] of its 16 x 4 piece, which
+// is the layout of both MFMA inputs, so a panel that is row side of one tile and column side of
+// another is read with the same addressing.  SLOTS (compile time) selects what is read at all.
+template <typename T, class Shape, uint32_t SLOTS>
+struct Operands {
+    T a[Shape::NA][4];
+    T b[Shape::NB];
+    __device__ __forceinline__ void load(const T* __restrict__ buf, int ks, int w, int lane)
+    {
+        constexpr int LDK = Cfg<T>::LDK;
+        const T* base = buf + (lane & 15) * LDK + (lane >> 4) + ks * 4;
+#pragma unroll
+        for (int i = 0; i < Shape::NA; ++i) {
+            if (!a_used<Shape>(SLOTS, i)) continue;
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) a[i][rb] = base[(Shape::a_panel(i) * kTile + rb * 16) * LDK];
+        }
+#pragma unroll
+        for (int j = 0; j < Shape::NB; ++j) {
+            if (!b_used<Shape>(SLOTS, j)) continue;
+            b[j] = base[(Shape::b_panel(j) * kTile + w * 16) * LDK];
+        }
+    }
+};
 
-// ---- one chunk of MFMA work for a triangle or rectangular block --------------------------------
-template <typename T, class Shape>
-__device__ __forceinline__ void compute_chunk(const T* __restrict__ buf,
-                                              typename Cfg<T>::acc_t (&acc)[Shape::NSLOT][4],
-                                              uint32_t pmask, int w, int lane)
+// MFMAs of one k-step for the slots of SLOTS that the run-time mask has.
+template <typename T, class Shape, uint32_t SLOTS>
+__device__ __forceinline__ void mfma_step(const Operands<T, Shape, SLOTS>& op,
+                                          typename Cfg<T>::acc_t (&acc)[Shape::NSLOT][4], uint32_t pmask)
 {
-    constexpr int KC = Cfg<T>::KC, LDK = Cfg<T>::LDK;
-    const int r16 = lane & 15, g = lane >> 4;
 #pragma unroll
-    for (int ks = 0; ks < KC / 4; ++ks) {
-        T a[Shape::NA][4], b[Shape::NB];
-#pragma unroll
-        for (int i = 0; i < Shape::NA; ++i)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb)
-                a[i][rb] = buf[(Shape::a_panel(i) * kTile + rb * 16 + r16) * LDK + ks * 4 + g];
+    for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
         for (int j = 0; j < Shape::NB; ++j)
-            b[j] = buf[(Shape::b_panel(j) * kTile + w * 16 + r16) * LDK + ks * 4 + g];
+            if (slot_on<Shape>(SLOTS, i, j)) {
+                const int s = Shape::slot(i, j);
+                if (pmask & (1u << s)) {
 #pragma unroll
-        for (int i = 0; i < Shape::NA; ++i)
-#pragma unroll
-            for (int j = 0; j < Shape::NB; ++j)
-                if (Shape::active(i, j)) {
-                    const int s = Shape::slot(i, j);
-                    if (pmask & (1u << s)) {
-#pragma unroll
-                        for (int rb = 0; rb < 4; ++rb)
-                            acc[s][rb] = Cfg<T>::mfma(a[i][rb], b[j], acc[s][rb]);
-                    }
+                    for (int rb = 0; rb < 4; ++rb)
+                        acc[s][rb] = Cfg<T>::mfma(op.a[i][rb], op.b[j], acc[s][rb]);
                 }
-    }
+            }
 }
+
+// ---- the main loop in assembly (generated) -----------------------------------------------------
+struct AsmLoopArgs {
+    uint32_t rd0, rd1;      // LDS byte address of the lane's row-side operand piece, buffer 0 / 1
+    uint32_t rb0, rb1;      // same for the column side (the wavefront's 16-row group)
+    uint32_t wr0, wr1;      // LDS byte address of the thread's first staged piece, buffer 0 / 1
+    const void* gR;         // row-side matrix
+    const void* gQ;         // column-side matrix
+    uint32_t nch;           // chunks, >= 1
+    uint32_t step;          // bytes per chunk along a row
+};
+#include "syrk_asm_loops.inc"
 
 // C tile element update: C <- beta*C + alpha*acc (beta == 0: C is not read)
 template <typename T>
@@ -202,39 +279,44 @@ __device__ __forceinline__ void store_subtile(const Mats<T>& m, int row0, int co
     }
 }
 
-template <typename T, class Shape>
-__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds)
+// One block from start to end.  LDS holds two chunks; registers hold the operands of two k-steps
+// and one chunk in flight from global memory.  Per chunk: the operands of k-step s+1 are read from
+// LDS before the MFMAs of k-step s are issued; before the last k-step the next chunk is written to
+// the other LDS buffer, the workgroup synchronises, the first operands of the next chunk are read
+// and the chunk after that is requested from global memory, all hidden behind the last k-step's
+// MFMAs.
+//   FAST: the slots SLOTS are exactly the block's, their panels are whole (64 rows inside the
+//   matrix), 16-byte loads are legal and M is a positive multiple of KC.  The chunk loop then has no
+//   test and no branch, so the accumulators stay in their registers across it.
+//   !FAST: anything else (ragged edges, odd leading dimensions, unusual slot sets); same schedule
+//   with every access checked.
+template <typename T, class Shape, uint32_t SLOTS, bool FAST>
+__device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
+                                           T* lds)
 {
-    constexpr int KC = Cfg<T>::KC, LDK = Cfg<T>::LDK, NP = Shape::NP;
+    constexpr int NP = Shape::NP;
+    constexpr int KC = Cfg<T>::KC, KS = KC / 4, LDK = Cfg<T>::LDK;
     constexpr int kBufElems = kMaxPanels * kTile * LDK;
+    constexpr uint32_t PANELS = panels_of<Shape>(SLOTS);
+    static_assert(KS % 2 == 0, "operand double buffering assumes an even number of k-steps");
     typedef typename Cfg<T>::acc_t acc_t;
+    typedef Operands<T, Shape, SLOTS> Ops;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // tile rows of the LDS panels, of the row side and of the column side of every slot
-    int prow[NP], arow[Shape::NA], brow[Shape::NB], nrows[NP];
+    int nrows[NP];
     const T* base[NP];
     int64_t ld[NP];
-    uint32_t pmask = 0;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-        prow[p] = it.rows[p];                               // -1: panel absent
         const bool col_side = Shape::col_side(p);
         base[p] = col_side ? m.Q : m.R;
         ld[p] = col_side ? m.ldq : m.ldr;
         nrows[p] = col_side ? m.nq : m.nr;
     }
-#pragma unroll
-    for (int i = 0; i < Shape::NA; ++i) arow[i] = prow[Shape::a_panel(i)];
-#pragma unroll
-    for (int j = 0; j < Shape::NB; ++j) brow[j] = prow[Shape::b_panel(j)];
-#pragma unroll
-    for (int i = 0; i < Shape::NA; ++i)
-#pragma unroll
-        for (int j = 0; j < Shape::NB; ++j)
-            if (Shape::active(i, j) && arow[i] >= 0 && brow[j] >= 0 && (!m.lower || brow[j] < arow[i]))
-                pmask |= 1u << Shape::slot(i, j);
+    Stager<T, NP, PANELS> st;
+    st.init(base, ld, nrows, prow, tid);
 
     acc_t acc[Shape::NSLOT][4];
 #pragma unroll
@@ -242,24 +324,68 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) acc[s][rb] = acc_t{0, 0, 0, 0};
 
-    const bool aligned = vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq);
     const int M = m.M;
     const int nchunks = (M + KC - 1) / KC;
-    Stager<T, NP> st;
-    if (nchunks > 0) {
-        st.load(base, ld, nrows, prow, M, 0, aligned && KC <= M, tid);
-        st.store(lds, tid);
-    }
-    __syncthreads();
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const bool more = ch + 1 < nchunks;
-        if (more) {
-            const int k0 = (ch + 1) * KC;
-            st.load(base, ld, nrows, prow, M, k0, aligned && k0 + KC <= M, tid);
+    if constexpr (FAST) {
+        // Addresses for the assembly loop: LDS offsets of the lane's operand pieces and of the
+        // thread's staging slots in both buffers, 32-bit byte offsets of the thread's pieces in
+        // global memory (the caller has checked that the matrices are smaller than 4 GiB).
+        constexpr int ES = (int)sizeof(T), VEC = Cfg<T>::VEC;
+        typedef __attribute__((address_space(3))) unsigned char lds_byte;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte*)lds;
+        AsmLoopArgs g;
+        g.rd0 = lds0 + (uint32_t)(((lane & 15) * LDK + (lane >> 4)) * ES);
+        g.rd1 = g.rd0 + (uint32_t)(kBufElems * ES);
+        g.rb0 = g.rd0 + (uint32_t)(w * 16 * LDK * ES);
+        g.rb1 = g.rb0 + (uint32_t)(kBufElems * ES);
+        g.wr0 = lds0 + (uint32_t)(((tid >> 3) * LDK + (tid & 7) * VEC) * ES);
+        g.wr1 = g.wr0 + (uint32_t)(kBufElems * ES);
+        g.gR = m.R;
+        g.gQ = m.Q;
+        g.nch = (uint32_t)nchunks;
+        g.step = (uint32_t)(KC * ES);
+        uint32_t go[10];
+        int q = 0;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            if (!((PANELS >> p) & 1u)) continue;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int64_t row = (int64_t)prow[p] * kTile + h * 32 + (tid >> 3);
+                go[q++] = (uint32_t)((row * ld[p] + (tid & 7) * VEC) * ES);
+            }
         }
-        compute_chunk<T, Shape>(lds + (ch & 1) * kBufElems, acc, pmask, w, lane);
-        if (more) st.store(lds + ((ch + 1) & 1) * kBufElems, tid);
+        AsmLoop<T, Shape, SLOTS>::run(acc, g, go);
+    } else {
+      if (nchunks > 0) {
+        const bool aligned = vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq);
+        st.load_checked(M, 0, aligned && KC <= M, tid);
+        st.store(lds, tid);
         __syncthreads();
+        if (nchunks > 1) st.load_checked(M, KC, aligned && 2 * KC <= M, tid);
+        Ops op[2];
+        op[0].load(lds, 0, w, lane);
+        for (int ch = 0; ch < nchunks; ++ch) {
+            T* cur = lds + (ch & 1) * kBufElems;
+            T* nxt = lds + ((ch + 1) & 1) * kBufElems;
+            const bool more = ch + 1 < nchunks;
+#pragma unroll
+            for (int ks = 0; ks < KS - 1; ++ks) {
+                op[(ks + 1) & 1].load(cur, ks + 1, w, lane);
+                mfma_step<T, Shape, SLOTS>(op[ks & 1], acc, pmask);
+            }
+            if (more) st.store(nxt, tid);
+            __syncthreads();
+            if (more) {
+                op[0].load(nxt, 0, w, lane);
+                if (ch + 2 < nchunks) {
+                    const int k0 = (ch + 2) * KC;
+                    st.load_checked(M, k0, aligned && k0 + KC <= M, tid);
+                }
+            }
+            mfma_step<T, Shape, SLOTS>(op[(KS - 1) & 1], acc, pmask);
+        }
+      }
     }
 
     const int col16 = w * 16 + (lane & 15);
@@ -267,22 +393,87 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
     for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
         for (int j = 0; j < Shape::NB; ++j)
-            if (Shape::active(i, j)) {
+            if (slot_on<Shape>(SLOTS, i, j)) {
                 const int s = Shape::slot(i, j);
-                if (pmask & (1u << s)) {
+                if (FAST || (pmask & (1u << s))) {
 #pragma unroll
                     for (int rb = 0; rb < 4; ++rb)
-                        store_subtile<T>(m, arow[i] * kTile + rb * 16, brow[j] * kTile + col16, acc[s][rb],
-                                         lane, false);
+                        store_subtile<T>(m, prow[Shape::a_panel(i)] * kTile + rb * 16,
+                                         prow[Shape::b_panel(j)] * kTile + col16, acc[s][rb], lane, false);
                 }
             }
+}
+
+// The slot sets that have a branch-free instance: a triangle block on 4, 3 or 2 tile rows; a
+// rectangle of r x c tiles, r <= 2, c <= 3.
+template <class Shape> struct FastSets;
+template <> struct FastSets<TriShape> {
+    static constexpr int N = 3;
+    static constexpr uint32_t set(int n) { return n == 0 ? 0x3Fu : n == 1 ? 0x07u : 0x01u; }
+};
+template <> struct FastSets<RectShape> {
+    static constexpr int N = 6;
+    static constexpr uint32_t set(int n)
+    {
+        return n == 0 ? 0x3Fu : n == 1 ? 0x1Bu : n == 2 ? 0x09u : n == 3 ? 0x07u : n == 4 ? 0x03u : 0x01u;
+    }
+};
+
+template <typename T, class Shape, int IDX>
+__device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
+                                         T* lds)
+{
+    if constexpr (IDX < FastSets<Shape>::N) {
+        constexpr uint32_t SLOTS = FastSets<Shape>::set(IDX);
+        if (pmask == SLOTS) {
+            constexpr uint32_t PANELS = panels_of<Shape>(SLOTS);
+            bool whole = true;
+#pragma unroll
+            for (int p = 0; p < Shape::NP; ++p)
+                if ((PANELS >> p) & 1u) {
+                    const int nrows = Shape::col_side(p) ? m.nq : m.nr;
+                    whole = whole && (prow[p] + 1) * kTile <= nrows;
+                }
+            if (!whole) return false;
+            block_body<T, Shape, SLOTS, true>(m, prow, pmask, lds);
+            return true;
+        }
+        return try_fast<T, Shape, IDX + 1>(m, prow, pmask, lds);
+    } else {
+        return false;
+    }
+}
+
+template <typename T, class Shape>
+__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds)
+{
+    constexpr int NP = Shape::NP;
+    int prow[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) prow[p] = it.rows[p];      // -1: panel absent
+    uint32_t pmask = 0;
+#pragma unroll
+    for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+        for (int j = 0; j < Shape::NB; ++j) {
+            const int ar = prow[Shape::a_panel(i)], br = prow[Shape::b_panel(j)];
+            if (Shape::active(i, j) && ar >= 0 && br >= 0 && (!m.lower || br < ar))
+                pmask |= 1u << Shape::slot(i, j);
+        }
+    constexpr int KC = Cfg<T>::KC;
+    const int64_t lim = (int64_t)1 << 32;                   // the assembly loop uses 32-bit byte offsets
+    const bool fast_ok = m.M >= KC && m.M % KC == 0 && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
+                         (int64_t)m.nr * m.ldr * (int64_t)sizeof(T) < lim &&
+                         (int64_t)m.nq * m.ldq * (int64_t)sizeof(T) < lim;
+    if (fast_ok && try_fast<T, Shape, 0>(m, prow, pmask, lds)) return;
+    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false>(m, prow, pmask, lds);
 }
 
 // ---- diagonal tile: 10 sub-tiles on or below the diagonal, at most 3 per wavefront -------------
 template <typename T>
 __device__ __forceinline__ void run_diag(const Item& it, const Mats<T>& m, T* lds)
 {
-    constexpr int KC = Cfg<T>::KC, LDK = Cfg<T>::LDK;
+    constexpr int KC = Cfg<T>::KC, KS = KC / 4, LDK = Cfg<T>::LDK;
     constexpr int kBufElems = kMaxPanels * kTile * LDK;
     typedef typename Cfg<T>::acc_t acc_t;
     const int tid = threadIdx.x;
@@ -290,7 +481,8 @@ __device__ __forceinline__ void run_diag(const Item& it, const Mats<T>& m, T* ld
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // (row group, column group) of the wavefront's sub-tiles:
     //   w0: (0,0) (1,0) (2,0)   w1: (1,1) (2,1) (3,1)   w2: (2,2) (3,2) (3,0)   w3: (3,3)
-    // (the two unused slots of wavefront 3 repeat (3,3) so that every LDS address stays valid)
+    // Wavefront 3 repeats (3,3) in its two spare slots and drops those results: the loop is the same
+    // straight-line code for every wavefront.
     const int nsub = (w == 3) ? 1 : 3;
     int srow[3], scol[3];
     srow[0] = w;
@@ -311,32 +503,33 @@ __device__ __forceinline__ void run_diag(const Item& it, const Mats<T>& m, T* ld
     const bool aligned = vec_ok(m.R, m.ldr);
     const int M = m.M;
     const int nchunks = (M + KC - 1) / KC;
-    Stager<T, 1> st;
+    Stager<T, 1, 1u> st;
+    st.init(base, ld, nrows, prow, tid);
     if (nchunks > 0) {
-        st.load(base, ld, nrows, prow, M, 0, aligned && KC <= M, tid);
+        st.load_checked(M, 0, aligned && KC <= M, tid);
         st.store(lds, tid);
     }
     __syncthreads();
-    const int r16 = lane & 15, g = lane >> 4;
+    const T* lane_base = lds + (lane & 15) * LDK + (lane >> 4);
     for (int ch = 0; ch < nchunks; ++ch) {
         const bool more = ch + 1 < nchunks;
         if (more) {
             const int k0 = (ch + 1) * KC;
-            st.load(base, ld, nrows, prow, M, k0, aligned && k0 + KC <= M, tid);
+            st.load_checked(M, k0, aligned && k0 + KC <= M, tid);
         }
-        const T* buf = lds + (ch & 1) * kBufElems;
+        const T* buf = lane_base + (ch & 1) * kBufElems;
+        T a[KS][3], b[KS][3];
 #pragma unroll
-        for (int ks = 0; ks < KC / 4; ++ks) {
-            T a[3], b[3];
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                a[s] = buf[(srow[s] * 16 + r16) * LDK + ks * 4 + g];
-                b[s] = buf[(scol[s] * 16 + r16) * LDK + ks * 4 + g];
+                a[ks][s] = buf[srow[s] * 16 * LDK + ks * 4];
+                b[ks][s] = buf[scol[s] * 16 * LDK + ks * 4];
             }
 #pragma unroll
-            for (int s = 0; s < 3; ++s)
-                if (s < nsub) acc[s] = Cfg<T>::mfma(a[s], b[s], acc[s]);
-        }
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) acc[s] = Cfg<T>::mfma(a[ks][s], b[ks][s], acc[s]);
         if (more) st.store(lds + ((ch + 1) & 1) * kBufElems, tid);
         __syncthreads();
     }
@@ -344,7 +537,7 @@ __device__ __forceinline__ void run_diag(const Item& it, const Mats<T>& m, T* ld
 #pragma unroll
     for (int s = 0; s < 3; ++s)
         if (s < nsub)
-            store_subtile<T>(m, t0 + srow[s] * 16, t0 + scol[s] * 16 + r16, acc[s], lane, true);
+            store_subtile<T>(m, t0 + srow[s] * 16, t0 + scol[s] * 16 + (lane & 15), acc[s], lane, true);
 }
 
 // ---- the kernels: workgroup index -> block -> code path ---------------------------------------
