@@ -31,6 +31,9 @@ def main():
                     "(C <- C - A A^T, A iid N(0,1)/sqrt(M)), for kernel studies")
     ap.add_argument("--square", action="store_true", help="time the square-block baseline instead")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--copy-bytes", type=int, default=0,
+                    help="instead of the benchmark: run a plain device copy of this many bytes --steps "
+                         "times (reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -45,6 +48,16 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     tb.load()                                    # fails loudly when the HIP library is missing
+
+    if args.copy_bytes > 0:
+        src = torch.ones(args.copy_bytes // 8, dtype=torch.float64, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": src.numel() * 8, "launches": args.steps}))
+        return 0
 
     if args.shape:
         n_, m_, dt_ = args.shape.split(",")

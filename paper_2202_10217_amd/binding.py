@@ -62,7 +62,7 @@ def load():
     lib.tbs_syrk_lower_query.restype = ctypes.c_int
     lib.tbs_syrk_lower_query.argtypes = [ctypes.c_int, i64, i64, i32, ctypes.POINTER(PlanInfo)]
     lib.tbs_syrk_lower_enumerate.restype = ctypes.c_int
-    lib.tbs_syrk_lower_enumerate.argtypes = [ctypes.c_int, i64, i32, p, i64, ctypes.POINTER(i64)]
+    lib.tbs_syrk_lower_enumerate.argtypes = [ctypes.c_int, i64, i64, i32, p, i64, ctypes.POINTER(i64)]
     lib.tbs_potrf_lower_workspace.restype = ctypes.c_int
     lib.tbs_potrf_lower_workspace.argtypes = [ctypes.c_int, i64, ctypes.POINTER(sz)]
     lib.tbs_potrf_lower.restype = ctypes.c_int
@@ -149,15 +149,15 @@ def tbs_syrk_lower_query(dtype_code, N, M, square=False) -> dict:
     return {name: getattr(info, name) for name, _ in PlanInfo._fields_}
 
 
-def tbs_syrk_lower_enumerate(dtype_code, N, square=False) -> np.ndarray:
+def tbs_syrk_lower_enumerate(dtype_code, N, M, square=False) -> np.ndarray:
     """The work list as an (n_items, 8) int32 array: kind, nrow, ncol, five tile-row slots."""
     lib = load()
     n = ctypes.c_int64(0)
-    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, int(bool(square)), None, 0, ctypes.byref(n))
+    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(bool(square)), None, 0, ctypes.byref(n))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_enumerate")
     out = np.empty((n.value, 8), dtype=np.int32)
-    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, int(bool(square)), out.ctypes.data, n.value,
+    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(bool(square)), out.ctypes.data, n.value,
                                       ctypes.byref(n))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_enumerate")

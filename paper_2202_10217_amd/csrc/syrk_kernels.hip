@@ -279,6 +279,41 @@ __device__ __forceinline__ void store_subtile(const Mats<T>& m, int row0, int co
     }
 }
 
+// The 16 elements of C that one lane holds of a 64 x 16 tile strip (4 row groups x 4 registers).
+template <typename T>
+struct TileStrip {
+    T v[4][4];
+    // CHECK: rows / columns beyond the matrix are skipped (ragged last tile)
+    template <bool CHECK>
+    __device__ __forceinline__ void load(const Mats<T>& m, int row0, int col, int lane)
+    {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int row = row0 + rb * 16 + Cfg<T>::row_of(g, lane);
+                v[rb][g] = (!CHECK || (row < m.nr && col < m.nq)) ? m.C[(int64_t)row * m.ldc + col] : T(0);
+            }
+    }
+};
+
+// Writes C <- beta*old + alpha*acc for one tile strip (beta == 0: old is not used).
+template <typename T, bool CHECK>
+__device__ __forceinline__ void store_strip(const Mats<T>& m, int row0, int col, int lane,
+                                            const typename Cfg<T>::acc_t (&acc)[4], const TileStrip<T>& old)
+{
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int row = row0 + rb * 16 + Cfg<T>::row_of(g, lane);
+            if (!CHECK || (row < m.nr && col < m.nq)) {
+                const T v = m.alpha * acc[rb][g];
+                m.C[(int64_t)row * m.ldc + col] = (m.beta != T(0)) ? m.beta * old.v[rb][g] + v : v;
+            }
+        }
+}
+
 // One block from start to end.  LDS holds two chunks; registers hold the operands of two k-steps
 // and one chunk in flight from global memory.  Per chunk: the operands of k-step s+1 are read from
 // LDS before the MFMAs of k-step s are issued; before the last k-step the next chunk is written to
@@ -388,20 +423,68 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
       }
     }
 
+    // Epilogue.  Every load of a tile strip is issued before any store of it, and (branch-free case)
+    // the loads of the next strip before the stores of the current one: the C traffic of a block is
+    // a handful of overlapped round trips, not one per sub-tile.
     const int col16 = w * 16 + (lane & 15);
+    if constexpr (FAST) {
+        TileStrip<T> old[2];
+        int first = -1;
 #pragma unroll
-    for (int i = 0; i < Shape::NA; ++i)
+        for (int s = 0; s < Shape::NSLOT; ++s)
+            if (first < 0 && ((SLOTS >> s) & 1u)) first = s;
+        int cur = 0;
+        const bool rd = m.beta != T(0);
 #pragma unroll
-        for (int j = 0; j < Shape::NB; ++j)
-            if (slot_on<Shape>(SLOTS, i, j)) {
-                const int s = Shape::slot(i, j);
-                if (FAST || (pmask & (1u << s))) {
+        for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
-                    for (int rb = 0; rb < 4; ++rb)
-                        store_subtile<T>(m, prow[Shape::a_panel(i)] * kTile + rb * 16,
-                                         prow[Shape::b_panel(j)] * kTile + col16, acc[s][rb], lane, false);
-                }
+            for (int j = 0; j < Shape::NB; ++j)
+                if (slot_on<Shape>(SLOTS, i, j) && Shape::slot(i, j) == first && rd)
+                    old[0].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
+                                                prow[Shape::b_panel(j)] * kTile + col16, lane);
+#pragma unroll
+        for (int s = 0; s < Shape::NSLOT; ++s) {
+            if (!((SLOTS >> s) & 1u)) continue;
+            // the next active slot, if any: prefetch its old values
+#pragma unroll
+            for (int s2 = s + 1; s2 < Shape::NSLOT; ++s2) {
+                bool is_next = ((SLOTS >> s2) & 1u) != 0;
+#pragma unroll
+                for (int s3 = s + 1; s3 < s2; ++s3) is_next = is_next && !((SLOTS >> s3) & 1u);
+                if (!is_next) continue;
+#pragma unroll
+                for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+                    for (int j = 0; j < Shape::NB; ++j)
+                        if (Shape::active(i, j) && Shape::slot(i, j) == s2 && rd)
+                            old[cur ^ 1].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
+                                                              prow[Shape::b_panel(j)] * kTile + col16, lane);
             }
+#pragma unroll
+            for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+                for (int j = 0; j < Shape::NB; ++j)
+                    if (Shape::active(i, j) && Shape::slot(i, j) == s)
+                        store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
+                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[s], old[cur]);
+            cur ^= 1;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+            for (int j = 0; j < Shape::NB; ++j)
+                if (slot_on<Shape>(SLOTS, i, j)) {
+                    const int s = Shape::slot(i, j);
+                    if (pmask & (1u << s)) {
+                        const int row0 = prow[Shape::a_panel(i)] * kTile;
+                        const int col = prow[Shape::b_panel(j)] * kTile + col16;
+                        TileStrip<T> old;
+                        if (m.beta != T(0)) old.template load<true>(m, row0, col, lane);
+                        store_strip<T, true>(m, row0, col, lane, acc[s], old);
+                    }
+                }
+    }
 }
 
 // The slot sets that have a branch-free instance: a triangle block on 4, 3 or 2 tile rows; a

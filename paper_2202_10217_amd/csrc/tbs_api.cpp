@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <map>
 #include <mutex>
+#include <tuple>
 #include <utility>
 
 #include "potrf_kernels.h"
@@ -25,17 +26,36 @@ constexpr int64_t kMaxM = (int64_t)1 << 30;
 bool dtype_ok(tbs_dtype d) { return d == TBS_F64 || d == TBS_F32; }
 size_t elem_size(tbs_dtype d) { return d == TBS_F32 ? 4 : 8; }
 
-// Plans depend on the number of tile rows only; they are built once and kept.
-const tbs::Plan* cached_plan(int32_t T, bool square)
+int32_t compute_units()
+{
+    static int32_t ncu = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;                                   // no device (host-only use): MI355X's count
+        return (int32_t)n;
+    }();
+    return ncu;
+}
+
+// A plan depends on the number of tile rows and, for small matrices, on how long a tile takes
+// compared with the fixed cost of a block (prologue, epilogue, dispatch: about 20 us against
+// M * 2 * 64 * 64 flops at one compute unit's share of the MFMA peak), which decides how finely the
+// tail of the work list is cut.  M enters through its power-of-two bucket.  Built once, kept.
+const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M)
 {
     static std::mutex mu;
-    static std::map<std::pair<int32_t, bool>, tbs::Plan> cache;
+    static std::map<std::tuple<int32_t, bool, int32_t, int32_t>, tbs::Plan> cache;
+    int32_t bucket = 0;
+    while (bucket < 30 && ((int64_t)3 << bucket) / 2 <= M) ++bucket;     // M ~ 2^bucket
     std::lock_guard<std::mutex> lock(mu);
-    auto key = std::make_pair(T, square);
+    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket);
     auto it = cache.find(key);
     if (it == cache.end()) {
+        const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
+        const double overhead_tiles = 20.0 / tile_us;
         tbs::Plan p;
-        if (!tbs::build_plan(T, square, &p)) return nullptr;
+        if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p)) return nullptr;
         it = cache.emplace(key, p).first;
     }
     return &it->second;
@@ -57,7 +77,7 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
 {
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, square);
+    const tbs::Plan* plan = cached_plan(T, square, dtype, M);
     if (!plan) return TBS_EINVAL;
     const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, stream);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
@@ -191,7 +211,7 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
 {
     if (!dtype_ok(dtype) || N < 0 || M < 0 || N > kMaxN || M > kMaxM || !out) return TBS_EINVAL;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, square != 0);
+    const tbs::Plan* plan = cached_plan(T, square != 0, dtype, M);
     if (!plan) return TBS_EINVAL;
     tbs::PlanStats st;
     tbs::plan_stats(*plan, N, M, &st);
@@ -220,12 +240,12 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
     return TBS_OK;
 }
 
-tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int32_t square, int32_t* items,
+tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32_t square, int32_t* items,
                                     int64_t capacity, int64_t* n_items)
 {
-    if (!dtype_ok(dtype) || N < 0 || N > kMaxN || !n_items) return TBS_EINVAL;
+    if (!dtype_ok(dtype) || N < 0 || N > kMaxN || M < 0 || M > kMaxM || !n_items) return TBS_EINVAL;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, square != 0);
+    const tbs::Plan* plan = cached_plan(T, square != 0, dtype, M);
     if (!plan) return TBS_EINVAL;
     *n_items = plan->n_items;
     if (!items) return TBS_OK;

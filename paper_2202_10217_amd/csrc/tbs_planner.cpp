@@ -3,7 +3,9 @@
 #include "tbs_planner.h"
 
 #include <algorithm>
+#include <functional>
 #include <numeric>
+#include <queue>
 #include <vector>
 
 namespace tbs {
@@ -20,13 +22,14 @@ int32_t choose_c(int32_t upper, int32_t k)
 
 namespace {
 
-Seg rect_seg(int32_t level, int64_t nz, int32_t r0, int32_t r1, int32_t c0, int32_t c1)
+Seg rect_seg(int32_t level, int64_t nz, int32_t r0, int32_t r1, int32_t c0, int32_t c1, int32_t mr,
+             int32_t nc)
 {
     Seg s{};
     s.kind = kSegRect;
     s.level = level;
     s.r0 = r0; s.r1 = r1; s.c0 = c0; s.c1 = c1;
-    s.mr = kRectRows; s.nc = kRectCols;
+    s.mr = mr; s.nc = nc;
     s.nI = (r1 - r0 + s.mr - 1) / s.mr;
     s.nJ = (c1 - c0 + s.nc - 1) / s.nc;
     s.count = (int32_t)(nz * s.nI * s.nJ);
@@ -35,26 +38,25 @@ Seg rect_seg(int32_t level, int64_t nz, int32_t r0, int32_t r1, int32_t c0, int3
 
 }  // namespace
 
-bool build_plan(int32_t T, bool square, Plan* out)
+bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
 {
     if (T < 0 || T > (1 << 15)) return false;
+    if (tune.mr < 1 || tune.mr > kRectRows || tune.nc < 1 || tune.nc > kRectCols) return false;
     Plan p{};
     p.k = kK;
     p.T = T;
     std::vector<Seg> tri, rect, base;
-    const int32_t k = p.k;
-    if (square) {
-        if (T >= 2) rect.push_back(rect_seg(0, 1, 0, T, 0, T - 1));
-    } else {
+    const int32_t k = p.k, mr = tune.mr, nc = tune.nc;
+    {
         int32_t level = 0, Tl = T;
         int64_t nz = 1;
         for (;;) {
             const int32_t c = choose_c(Tl / k, k);
-            const bool room = level < kMaxLevels - 1 &&
+            const bool room = level < kMaxLevels - 1 && level < tune.tri_levels &&
                               (int)(tri.size() + rect.size()) + 3 < kMaxSegs - 2;
             if (c < k - 1 || !room) {                       // base zones (c too small)
                 if (Tl >= 2) {
-                    if (Tl <= k) {
+                    if (Tl <= k && tune.tri_base) {
                         Seg s{};
                         s.kind = kSegTriBase;
                         s.level = level;
@@ -62,7 +64,7 @@ bool build_plan(int32_t T, bool square, Plan* out)
                         s.count = (int32_t)nz;
                         base.push_back(s);
                     } else {
-                        rect.push_back(rect_seg(level, nz, 0, Tl, 0, Tl - 1));
+                        rect.push_back(rect_seg(level, nz, 0, Tl, 0, Tl - 1, mr, nc));
                     }
                 }
                 break;
@@ -75,8 +77,8 @@ bool build_plan(int32_t T, bool square, Plan* out)
             tri.push_back(s);
             const int32_t done = k * c, l = Tl - done;
             if (l > 0) {                                    // the last l tile rows
-                rect.push_back(rect_seg(level, nz, done, Tl, 0, done));
-                if (l >= 2) rect.push_back(rect_seg(level, nz, done, Tl, done, Tl - 1));
+                rect.push_back(rect_seg(level, nz, done, Tl, 0, done, mr, nc));
+                if (l >= 2) rect.push_back(rect_seg(level, nz, done, Tl, done, Tl - 1, mr, nc));
             }
             nz *= k;
             Tl = c;
@@ -84,6 +86,7 @@ bool build_plan(int32_t T, bool square, Plan* out)
         }
     }
     // longest blocks first: triangle blocks by level, rectangles, base triangles, diagonal tiles
+    // (a base triangle of k rows is as long as a family block: it goes before the rectangles then)
     int32_t n = 0, first = 0;
     auto push = [&](Seg s) {
         if (s.count <= 0) return;
@@ -91,9 +94,17 @@ bool build_plan(int32_t T, bool square, Plan* out)
         first += s.count;
         p.seg[n++] = s;
     };
-    for (const Seg& s : tri) push(s);
-    for (const Seg& s : rect) push(s);
-    for (const Seg& s : base) push(s);
+    std::vector<Seg> all(tri);
+    all.insert(all.end(), rect.begin(), rect.end());
+    all.insert(all.end(), base.begin(), base.end());
+    auto tiles_of = [&](const Seg& s) {
+        if (s.kind == kSegTri) return k * (k - 1) / 2;
+        if (s.kind == kSegTriBase) return s.r1 * (s.r1 - 1) / 2;
+        return s.mr * s.nc;
+    };
+    std::stable_sort(all.begin(), all.end(),
+                     [&](const Seg& a, const Seg& b) { return tiles_of(a) > tiles_of(b); });
+    for (const Seg& s : all) push(s);
     if (T > 0) {
         Seg d{};
         d.kind = kSegDiag;
@@ -103,6 +114,61 @@ bool build_plan(int32_t T, bool square, Plan* out)
     p.nseg = n;
     p.n_items = first;
     *out = p;
+    return true;
+}
+
+double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
+{
+    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+    for (int32_t u = 0; u < ncu; ++u) free_at.push(0.0);
+    double end = 0.0;
+    for (int32_t t = 0; t < p.n_items; ++t) {
+        Item it;
+        tbs_decode(p, t, it);
+        double tiles = 0.0;
+        if (it.kind == kTri) {
+            tiles = 0.5 * it.nrow * (it.nrow - 1);
+        } else if (it.kind == kRect) {
+            for (int r = 0; r < kRectRows; ++r)
+                for (int q = 0; q < kRectCols; ++q)
+                    if (it.rows[kRectCols + r] >= 0 && it.rows[q] >= 0 && it.rows[q] < it.rows[kRectCols + r])
+                        tiles += 1.0;
+        } else if (it.kind == kDiag) {
+            tiles = 10.0 / 16.0;
+        } else {
+            continue;                                       // empty block: exits at once
+        }
+        const double start = free_at.top();
+        free_at.pop();
+        const double stop = start + tiles + overhead_tiles;
+        free_at.push(stop);
+        end = std::max(end, stop);
+    }
+    return end;
+}
+
+bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out)
+{
+    if (square) return build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out);
+    const PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
+    if (!build_plan(T, coarse, out)) return false;
+    // with many blocks per compute unit the granularity of the tail does not matter
+    const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
+    if (per_unit > 200.0 || T < 2) return true;
+    double best = simulate_makespan(*out, ncu, overhead_tiles);
+    const int32_t shapes[4][2] = {{2, 3}, {1, 3}, {1, 2}, {1, 1}};
+    for (int32_t levels = kMaxLevels; levels >= 0; levels = (levels == kMaxLevels) ? 2 : levels - 1) {
+        for (const auto& sh : shapes) {
+            const PlanTuning tune{levels, sh[0], sh[1], levels == kMaxLevels && sh[0] == 2};
+            Plan cand;
+            if (!build_plan(T, tune, &cand)) continue;
+            const double span = simulate_makespan(cand, ncu, overhead_tiles);
+            if (span < best * 0.98) {                       // prefer the coarser plan on near ties
+                best = span;
+                *out = cand;
+            }
+        }
+    }
     return true;
 }
 

@@ -8,9 +8,28 @@ namespace tbs {
 // Section 5.1.2 for the cyclic family); 0 when upper <= 0.
 int32_t choose_c(int32_t upper, int32_t k);
 
-// Plan for a matrix of T tile rows.  square = true: rectangular blocks only (the baseline).
-// Returns false when T is out of range for the descriptor.
-bool build_plan(int32_t T, bool square, Plan* out);
+// How a plan covers what the top-level triangle blocks leave: how many recursion levels use
+// triangle blocks, the shape of the rectangular blocks, whether a base zone of at most k tile rows
+// is one triangle block.
+struct PlanTuning {
+    int32_t tri_levels;      // levels that use triangle blocks (0: none, i.e. rectangles only)
+    int32_t mr, nc;          // rectangular block: mr x nc tiles, mr <= kRectRows, nc <= kRectCols
+    bool tri_base;           // base zones of <= k tile rows become one triangle block
+};
+
+// Plan for a matrix of T tile rows with the given tuning.  Returns false when T is out of range for
+// the descriptor.
+bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
+
+// The plan the library uses.  square = true: rectangular 2 x 3 blocks only (the baseline).
+// Otherwise the schedule of Algorithm 4; for small matrices, where a compute unit receives only a
+// few blocks, the candidates differ in how finely the diagonal zones and the last tile rows are cut,
+// and the one with the shortest simulated makespan on `ncu` compute units is taken (blocks are
+// dispatched in list order to the first free unit; a block costs its tiles plus `overhead_tiles`).
+bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out);
+
+// Makespan, in tile units, of dispatching the plan's blocks in order onto ncu units.
+double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles);
 
 struct PlanStats {
     int32_t levels;

@@ -90,8 +90,8 @@ def test_query_and_enumerate_reject_bad_arguments(lib):
     with pytest.raises(tb.TbsError):
         tb.tbs_syrk_lower_query(tb.TBS_F64, -5, 3)
     with pytest.raises(tb.TbsError):
-        tb.tbs_syrk_lower_enumerate(9, 100)
+        tb.tbs_syrk_lower_enumerate(9, 100, 10)
     n = ctypes.c_int64(0)
     buf = (ctypes.c_int32 * 8)()
-    st = lib.tbs_syrk_lower_enumerate(0, 4096, 0, buf, 1, ctypes.byref(n))
+    st = lib.tbs_syrk_lower_enumerate(0, 4096, 4096, 0, buf, 1, ctypes.byref(n))
     assert st == tb.TBS_EWORKSPACE and n.value > 1
