@@ -18,7 +18,10 @@ import numpy as np
 PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}       # MI355X dense matrix peaks, TFLOP/s
 # HBM bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel
 # of known size); filled in from the summaries under profiles/ for the workloads measured there.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/tbs_syrk_kernel_f64_n4096_m4096.md: 2.728e9 read + 6.717e7 written
+    ("syrk_n4096_m4096_f64", False): 2.795e9,
+}
 
 
 def main():
