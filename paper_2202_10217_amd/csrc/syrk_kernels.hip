@@ -55,8 +55,11 @@ template <> struct Cfg<float> {
     static __device__ __forceinline__ int row_of(int g, int lane) { return 4 * (lane >> 4) + g; }
 };
 
-constexpr int kLdsBytes = 2 * kMaxPanels * kTile * Cfg<double>::LDK * 8;
-static_assert(kLdsBytes == 2 * kMaxPanels * kTile * Cfg<float>::LDK * 4, "one LDS size for both types");
+// LDS: the assembly loops use a ring of chunk buffers (144 KB of the 160 KB a compute unit has); the
+// checked C++ loop uses two padded buffers at the start of the same allocation.
+constexpr int kLdsBytes = 144 * 1024;
+static_assert(2 * kMaxPanels * kTile * Cfg<double>::LDK * 8 <= kLdsBytes, "checked path fits");
+static_assert(2 * kMaxPanels * kTile * Cfg<float>::LDK * 4 <= kLdsBytes, "checked path fits");
 
 // ---- block shapes ----------------------------------------------------------------------------
 // A shape names which LDS panels feed the row side (all four 16-row groups of a panel) and the
@@ -246,13 +249,13 @@ __device__ __forceinline__ void mfma_step(const Operands<T, Shape, SLOTS>& op,
 
 // ---- the main loop in assembly (generated) -----------------------------------------------------
 struct AsmLoopArgs {
-    uint32_t rd0, rd1;      // LDS byte address of the lane's row-side operand piece, buffer 0 / 1
-    uint32_t rb0, rb1;      // same for the column side (the wavefront's 16-row group)
-    uint32_t wr0, wr1;      // LDS byte address of the thread's first staged piece, buffer 0 / 1
+    uint32_t ada[8];        // LDS byte address of the lane's row-side operand piece for k-step j
+    uint32_t adb[8];        // same for the column side (includes the wavefront's 16-row group)
     const void* gR;         // row-side matrix
     const void* gQ;         // column-side matrix
     uint32_t nch;           // chunks, >= 1
     uint32_t step;          // bytes per chunk along a row
+    uint32_t m0base;        // LDS byte address of the wavefront's 1 KB slice in panel 0, half 0, buffer 0
 };
 #include "syrk_asm_loops.inc"
 
@@ -362,23 +365,32 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     const int M = m.M;
     const int nchunks = (M + KC - 1) / KC;
     if constexpr (FAST) {
-        // Addresses for the assembly loop: LDS offsets of the lane's operand pieces and of the
-        // thread's staging slots in both buffers, 32-bit byte offsets of the thread's pieces in
-        // global memory (the caller has checked that the matrices are smaller than 4 GiB).
-        constexpr int ES = (int)sizeof(T), VEC = Cfg<T>::VEC;
+        // Addresses for the assembly loop (layout and schedule: gen_asm_loops.py).  In LDS a chunk
+        // buffer holds the used panels back to back, 64 rows of 128 bytes each, the 16-byte pieces of
+        // row r permuted by XOR with r mod 8.  The caller has checked that the matrices are smaller
+        // than 4 GiB: global offsets are 32-bit.
+        constexpr int ES = (int)sizeof(T);
         typedef __attribute__((address_space(3))) unsigned char lds_byte;
         const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte*)lds;
         AsmLoopArgs g;
-        g.rd0 = lds0 + (uint32_t)(((lane & 15) * LDK + (lane >> 4)) * ES);
-        g.rd1 = g.rd0 + (uint32_t)(kBufElems * ES);
-        g.rb0 = g.rd0 + (uint32_t)(w * 16 * LDK * ES);
-        g.rb1 = g.rb0 + (uint32_t)(kBufElems * ES);
-        g.wr0 = lds0 + (uint32_t)(((tid >> 3) * LDK + (tid & 7) * VEC) * ES);
-        g.wr1 = g.wr0 + (uint32_t)(kBufElems * ES);
+        {
+            const uint32_t r16 = lane & 15, gq = lane >> 4, x = r16 & 7;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                uint32_t a;
+                if (ES == 8)       // element k = 4 ks + gq: piece (2 ks + gq/2) ^ x, half gq & 1
+                    a = r16 * 128 + ((((gq >> 1) ^ (x & 1)) | (((uint32_t)j ^ (x >> 1)) << 1)) << 4) + (gq & 1) * 8;
+                else               // element k = 4 ks + gq: piece ks ^ x, word gq
+                    a = r16 * 128 + (((uint32_t)j ^ x) << 4) + gq * 4;
+                g.ada[j] = lds0 + a;
+                g.adb[j] = lds0 + a + (uint32_t)w * 2048;
+            }
+        }
         g.gR = m.R;
         g.gQ = m.Q;
         g.nch = (uint32_t)nchunks;
         g.step = (uint32_t)(KC * ES);
+        g.m0base = lds0 + (uint32_t)w * 1024;
         uint32_t go[10];
         int q = 0;
 #pragma unroll
@@ -386,8 +398,10 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
             if (!((PANELS >> p) & 1u)) continue;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int64_t row = (int64_t)prow[p] * kTile + h * 32 + (tid >> 3);
-                go[q++] = (uint32_t)((row * ld[p] + (tid & 7) * VEC) * ES);
+                // this lane's piece of the wavefront's 8 rows: row 8w + lane/8 of the half-panel,
+                // global piece (lane%8) ^ (lane/8) so that it lands at LDS position lane%8
+                const int64_t row = (int64_t)prow[p] * kTile + h * 32 + w * 8 + (lane >> 3);
+                go[q++] = (uint32_t)(row * ld[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
             }
         }
         AsmLoop<T, Shape, SLOTS>::run(acc, g, go);
