@@ -11,67 +11,111 @@ namespace tbs {
 constexpr int kPT = 64;          // tile side
 constexpr int kPLd = kPT + 1;    // padded LDS row
 
+// Thread (i, q) = (tid / 4, tid % 4) keeps the elements j = 4 m + q, m = 0..15, of row i of the
+// working matrix S and of the inverse X in registers for the whole factorisation.  A step needs two
+// things from other threads, both broadcast through LDS: the scaled column k of L (stored so that
+// the 16 values a thread needs are contiguous) and row k of X.  The elimination loop is unrolled
+// completely, so every register index is a constant and a step only touches the columns that still
+// change (j > k of S, j <= k of X).
+//
+// The operations on S are those of Algorithm 2 in its order (pivot, scale column k by division,
+// rank-1 update with the scaled column), so integer-valued factors come out exactly.  The inverse is
+// built in the same sweep: L X = I solved by eliminating column k of L from the rows below row k.
+// One elimination step; K is a compile-time constant so that every register index is static.
+template <typename T, int K>
+__device__ __forceinline__ void tile_step(T (&s)[16], T (&x)[16], T* colL, T* rowX, T* pivot, int& fail,
+                                          int i, int q, int perm_i)
+{
+    constexpr int km = K >> 2, kq = K & 3;
+    T p = *pivot;
+    if (!(p > T(0))) {                                      // uniform: every thread reads the same p
+        if (fail < 0) fail = K;
+        p = T(1);                                           // keep going on finite numbers; the output
+    }                                                       // from column `fail` on is unspecified
+    const T d = sqrt(p);
+    if (q == kq) {                                          // owners of column K
+        const T a = s[km];
+        const T l = (i > K) ? a / d : d;
+        if (i >= K) s[km] = l;
+        colL[perm_i] = (i > K) ? l : T(0);
+    }
+    if (i == K) {                                           // owners of row K of X
+        const T r = T(1) / d;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            if (m <= km) x[m] *= r;
+            rowX[q * 16 + m] = x[m];
+        }
+    }
+    __syncthreads();
+    if ((i | 15) > K) {                                     // wavefronts whose 16 rows are all <= K idle
+        const T lik = colL[perm_i];
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            if (m >= km) s[m] -= lik * colL[q * 16 + m];    // columns j > K (entries for j <= K are 0)
+            if (m <= km) x[m] -= lik * rowX[q * 16 + m];    // columns j <= K
+        }
+    }
+    if (K + 1 < kPT && i == K + 1 && q == ((K + 1) & 3)) *pivot = s[((K + 1) >> 2) & 15];
+    __syncthreads();
+}
+
+template <typename T, int K>
+struct TileSteps {
+    static __device__ __forceinline__ void run(int nb, T (&s)[16], T (&x)[16], T* colL, T* rowX, T* pivot,
+                                               int& fail, int i, int q, int perm_i)
+    {
+        if constexpr (K < kPT) {
+            if (K < nb) {                                   // uniform
+                tile_step<T, K>(s, x, colL, rowX, pivot, fail, i, q, perm_i);
+                TileSteps<T, K + 1>::run(nb, s, x, colL, rowX, pivot, fail, i, q, perm_i);
+            }
+        }
+    }
+};
+
+// Thread (i, q) = (tid / 4, tid % 4) keeps the elements j = 4 m + q, m = 0..15, of row i of the
+// working matrix S and of the inverse X in registers for the whole factorisation.  A step needs two
+// things from other threads, both broadcast through LDS: the scaled column k of L (stored so that
+// the 16 values a thread needs are contiguous) and row k of X.  The elimination loop is unrolled
+// completely (template recursion), so every register index is a constant and a step only touches
+// the columns that still change (j > k of S, j <= k of X).
+//
+// The operations on S are those of Algorithm 2 in its order (pivot, scale column k by division,
+// rank-1 update with the scaled column), so integer-valued factors come out exactly.  The inverse is
+// built in the same sweep: L X = I solved by eliminating column k of L from the rows below row k.
 template <typename T>
 __global__ __launch_bounds__(256) void potrf_tile_kernel(int nb, T* __restrict__ A, int64_t lda,
                                                          T* __restrict__ Linv, int32_t* info, int32_t index0)
 {
-    __shared__ T S[kPT * kPLd];      // working copy, trailing part updated in place
-    __shared__ T L[kPT * kPLd];      // finished factor
-    __shared__ T X[kPT * kPLd];      // inverse of the factor
-    __shared__ int s_fail;
+    __shared__ T colL[kPT];          // scaled column k, entry of row j at [(j % 4) * 16 + j / 4]; 0 for j <= k
+    __shared__ T rowX[kPT];          // row k of X, same permutation; 0 for j > k
+    __shared__ T pivot;              // S[k][k] entering step k
     const int tid = threadIdx.x;
-    if (tid == 0) s_fail = -1;
-    for (int e = tid; e < kPT * kPT; e += 256) {
-        const int i = e / kPT, j = e - i * kPT;
+    const int i = tid >> 2, q = tid & 3;
+    const int perm_i = (i & 3) * 16 + (i >> 2);
+    T s[16], x[16];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+        const int j = 4 * m + q;
         T v = (i == j) ? T(1) : T(0);                      // identity padding beyond nb
         if (i < nb && j <= i) v = A[(int64_t)i * lda + j];
-        S[i * kPLd + j] = v;
-        L[i * kPLd + j] = (i == j) ? T(1) : T(0);
+        s[m] = v;
+        x[m] = (i == j) ? T(1) : T(0);
     }
+    if (tid == 0) pivot = s[0];
+    int fail = -1;
     __syncthreads();
-    // right-looking elimination in the order of Algorithm 2: pivot, scale column k, rank-1 update of
-    // the trailing matrix with the scaled column (the same operations on the same values as the plain
-    // loops, so integer-valued factors come out exactly).
-    const int ti = tid >> 2, tj0 = tid & 3;
-    for (int k = 0; k < nb; ++k) {
-        const T p = S[k * kPLd + k];
-        if (!(p > T(0))) {
-            if (tid == 0) s_fail = k;
-            break;                                          // p is the same for every thread
-        }
-        const T d = sqrt(p);
-        if (tid >= k && tid < nb) L[tid * kPLd + k] = (tid == k) ? d : S[tid * kPLd + k] / d;
-        __syncthreads();
-        if (ti > k && ti < nb) {
-            const T lik = L[ti * kPLd + k];
-            for (int j = k + 1 + tj0; j <= ti; j += 4) S[ti * kPLd + j] -= lik * L[j * kPLd + k];
-        }
-        __syncthreads();
-    }
-    __syncthreads();
-    const int fail = s_fail;
-    if (fail >= 0) {
-        if (tid == 0 && *info == 0) *info = index0 + fail + 1;
-    }
-    // write back the columns that were finished (all of them when nothing failed)
+    TileSteps<T, 0>::run(nb, s, x, colL, rowX, &pivot, fail, i, q, perm_i);
+    if (fail >= 0 && tid == 0 && *info == 0) *info = index0 + fail + 1;
+    // write back the columns that were finished (all of them when nothing failed); the inverse is
+    // meaningful only then
     const int ncol = (fail >= 0) ? fail : nb;
-    for (int e = tid; e < kPT * kPT; e += 256) {
-        const int i = e / kPT, j = e - i * kPT;
-        if (i < nb && j <= i && j < ncol) A[(int64_t)i * lda + j] = L[i * kPLd + j];
-    }
-    // inverse of L by forward substitution, one column per thread: L x = e_j
-    if (tid < kPT) {
-        const int j = tid;
-        for (int i = 0; i < kPT; ++i) {
-            T s = (i == j) ? T(1) : T(0);
-            for (int m = j; m < i; ++m) s -= L[i * kPLd + m] * X[m * kPLd + j];
-            X[i * kPLd + j] = (i < j) ? T(0) : s / L[i * kPLd + i];
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < kPT * kPT; e += 256) {
-        const int i = e / kPT, j = e - i * kPT;
-        Linv[i * kPT + j] = X[i * kPLd + j];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+        const int j = 4 * m + q;
+        if (i < nb && j <= i && j < ncol) A[(int64_t)i * lda + j] = s[m];
+        Linv[i * kPT + j] = (j <= i) ? x[m] : T(0);
     }
 }
 
