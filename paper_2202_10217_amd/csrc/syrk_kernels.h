@@ -7,10 +7,12 @@
 
 namespace tbs {
 
-// C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`; one workgroup per block.
-// All pointers are device pointers; sizes have been validated by the caller.
+// C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`.  All pointers are device pointers; sizes
+// have been validated by the caller.  max_workgroups > 0 bounds the launch: a plan with more blocks
+// runs as that many persistent workgroups taking blocks in list order (normally the number of
+// compute units; fewer leaves units free for kernels of other streams); <= 0: one workgroup per block.
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                       int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream);
+                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, hipStream_t stream);
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, all row-major device matrices.  C may alias
 // R when n <= 192 and every workgroup's rows of R are only its own rows of C (the in-place

@@ -14,6 +14,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "tbs_plan.h"
 #include "syrk_kernels.h"
 
@@ -637,17 +640,12 @@ __device__ __forceinline__ void run_diag(const Item& it, const Mats<T>& m, T* ld
             store_subtile<T>(m, t0 + srow[s] * 16, t0 + scol[s] * 16 + (lane & 15), acc[s], lane, true);
 }
 
-// ---- the kernels: workgroup index -> block -> code path ---------------------------------------
+// ---- the kernels: workgroup -> block(s) -> code path ------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, int M, T alpha,
-                                                            const T* __restrict__ A, int64_t lda,
-                                                            T beta, T* __restrict__ C, int64_t ldc)
+__device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mats<T>& m, T* lds)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
-    T* lds = reinterpret_cast<T*>(smem);
     Item it;
-    tbs_decode(plan, (int32_t)blockIdx.x, it);
-    const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
+    tbs_decode(plan, id, it);
     if (it.kind == kTri) {
         run_block<T, TriShape>(it, m, lds);
     } else if (it.kind == kRect) {
@@ -656,6 +654,56 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, in
         run_diag<T>(it, m, lds);
     }
 }
+
+// One workgroup per block of the plan (used when the plan has no more blocks than the launch may
+// have workgroups).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, int M, T alpha,
+                                                            const T* __restrict__ A, int64_t lda,
+                                                            T beta, T* __restrict__ C, int64_t ldc)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
+    const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
+    run_item<T>(plan, (int32_t)blockIdx.x, m, reinterpret_cast<T*>(smem));
+}
+
+// Persistent form: a fixed number of workgroups (at most one per compute unit; fewer when the caller
+// wants to keep units free for kernels of another stream) take blocks from the list in order through
+// a counter in device memory, which is what the hardware dispatcher does with one workgroup per
+// block, minus the cost of starting a workgroup for every block.  ctr[0] = next block, ctr[1] =
+// workgroups that have finished; the last one to finish sets both back to zero for the next launch
+// that uses the same pair.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, int N, int M, T alpha,
+                                                                       const T* __restrict__ A, int64_t lda,
+                                                                       T beta, T* __restrict__ C, int64_t ldc,
+                                                                       unsigned int* ctr)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
+    __shared__ int32_t s_item;
+    const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
+    for (;;) {
+        __syncthreads();                        // the previous block's LDS reads and s_item are done with
+        if (threadIdx.x == 0) s_item = (int32_t)atomicAdd(&ctr[0], 1u);
+        __syncthreads();
+        const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
+        if (id >= plan.n_items) break;
+        run_item<T>(plan, id, m, reinterpret_cast<T*>(smem));
+    }
+    if (threadIdx.x == 0) {
+        __threadfence();
+        if (atomicAdd(&ctr[1], 1u) == gridDim.x - 1) {  // every workgroup has left its loop
+            ctr[0] = 0u;
+            ctr[1] = 0u;
+            __threadfence();
+        }
+    }
+}
+
+// Counter pairs for persistent launches, zero at load time and zero again after every launch.
+// Launches that may run at the same time must use different pairs: they are handed out round robin.
+constexpr int kCounterPairs = 64;
+__device__ unsigned int g_syrk_counters[kCounterPairs][2];
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, rectangular blocks of 2 x 3 tiles.
 template <typename T>
@@ -687,19 +735,43 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
 
 template <typename T>
 static hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                                int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream)
+                                int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups,
+                                hipStream_t stream)
 {
     if (plan.n_items <= 0) return hipSuccess;
-    hipLaunchKernelGGL(tbs_syrk_kernel<T>, dim3((unsigned)plan.n_items), dim3(kThreads), 0, stream, plan,
-                       (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc);
+    if (max_workgroups <= 0 || plan.n_items <= max_workgroups) {
+        hipLaunchKernelGGL(tbs_syrk_kernel<T>, dim3((unsigned)plan.n_items), dim3(kThreads), 0, stream, plan,
+                           (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc);
+        return hipGetLastError();
+    }
+    // address of the counter array on the current device, looked up once per device
+    static std::mutex mu;
+    static unsigned int* base[64] = {nullptr};
+    static std::atomic<unsigned> next_pair{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!base[dev]) {
+            void* ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_syrk_counters));
+            if (e != hipSuccess) return e;
+            base[dev] = static_cast<unsigned int*>(ptr);
+        }
+    }
+    unsigned int* ctr = base[dev] + 2 * (next_pair.fetch_add(1) % kCounterPairs);
+    hipLaunchKernelGGL(tbs_syrk_persistent_kernel<T>, dim3((unsigned)max_workgroups), dim3(kThreads), 0, stream,
+                       plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc, ctr);
     return hipGetLastError();
 }
 
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                       int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream)
+                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, hipStream_t stream)
 {
-    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, stream)
-               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, stream);
+    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, stream)
+               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, stream);
 }
 
 template <typename T>

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <map>
@@ -73,13 +74,19 @@ tbs_status check_syrk(tbs_dtype dtype, int64_t N, int64_t M, const void* A, int6
 }
 
 tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,
-                     int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream)
+                     int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream, int reserve_units = 0)
 {
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
     const tbs::Plan* plan = cached_plan(T, square, dtype, M);
     if (!plan) return TBS_EINVAL;
-    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, stream);
+    static const bool persistent = [] {
+        const char* v = std::getenv("TBS_SYRK_PERSISTENT");
+        return !(v && v[0] == '0');
+    }();
+    const int wgs = persistent ? std::max(1, compute_units() - reserve_units) : 0;
+    const hipError_t e =
+        tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, wgs, stream);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 
