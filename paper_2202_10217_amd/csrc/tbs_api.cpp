@@ -93,6 +93,31 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
 // ---- Large Block Cholesky ------------------------------------------------------------------------
 constexpr size_t kInfoBytes = 256;                     // info word, padded to keep the rest aligned
 
+// A second stream and two events per device for the look-ahead of Large Block Cholesky (created on
+// first use, default priority, kept until the process ends).
+struct LookAhead {
+    hipStream_t panel = nullptr;
+    hipEvent_t column_ready = nullptr, panel_done = nullptr;
+    bool ok = false;
+};
+
+LookAhead* look_ahead_for_device()
+{
+    static std::mutex mu;
+    static std::map<int, LookAhead> per_device;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    LookAhead& la = per_device[dev];
+    if (!la.ok) {
+        if (hipStreamCreateWithFlags(&la.panel, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&la.column_ready, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&la.panel_done, hipEventDisableTiming) != hipSuccess) return nullptr;
+        la.ok = true;
+    }
+    return &la;
+}
+
 struct Lbc {
     tbs_dtype dtype;
     size_t es;
@@ -100,13 +125,15 @@ struct Lbc {
     int64_t lda;
     char* linv;          // one 64 x 64 inverse per diagonal tile
     int32_t* info;
-    hipStream_t stream;
+    hipStream_t stream;  // the caller's stream
     int64_t big_block;   // panel width at the top level
+    int reserve_units;   // compute units the trailing update leaves to the panel stream
     hipError_t err = hipSuccess;
 
     char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
     char* inv_of(int64_t row) const { return linv + (size_t)(row / kTile) * kTile * kTile * es; }
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+    void note(tbs_status st) { if (st != TBS_OK) note(hipErrorUnknown); }
 
     int64_t block_for(int64_t n) const
     {
@@ -119,45 +146,95 @@ struct Lbc {
     // X = A[row0 : row0+m, col0 : col0+nb]  <-  X * L^{-T},  L = A[col0 : col0+nb, col0 : col0+nb]
     // (the solve of Algorithm 5, "TRSM"): recursive on the column blocks of L; a 64-wide block is
     // solved by multiplying with the inverse of its diagonal tile.
-    void trsm(int64_t row0, int64_t m, int64_t col0, int64_t nb)
+    void trsm(int64_t row0, int64_t m, int64_t col0, int64_t nb, hipStream_t st)
     {
         if (m <= 0 || nb <= 0) return;
         const bool f32 = dtype == TBS_F32;
         if (nb <= kTile) {
             note(tbs::launch_gemm_nt(f32, m, nb, nb, 1.0, at(row0, col0), lda, inv_of(col0), kTile, 0.0,
-                                     at(row0, col0), lda, stream));
+                                     at(row0, col0), lda, st));
             return;
         }
         const int64_t nb1 = ((nb / kTile + 1) / 2) * kTile;
-        trsm(row0, m, col0, nb1);
+        trsm(row0, m, col0, nb1, st);
         note(tbs::launch_gemm_nt(f32, m, nb - nb1, nb1, -1.0, at(row0, col0), lda, at(col0 + nb1, col0), lda,
-                                 1.0, at(row0, col0 + nb1), lda, stream));
-        trsm(row0, m, col0 + nb1, nb - nb1);
+                                 1.0, at(row0, col0 + nb1), lda, st));
+        trsm(row0, m, col0 + nb1, nb - nb1, st);
     }
 
-    // Algorithm 5 on A[off : off+n, off : off+n]; the one-tile Cholesky of the panel is the same
-    // routine with a smaller block (the recursive variant the paper mentions in Section 5.2.1).
-    void potrf(int64_t off, int64_t n)
+    // Algorithm 5 on A[off : off+n, off : off+n], everything on one stream; the one-tile Cholesky of
+    // the panel is the same routine with a smaller block (the recursive variant the paper mentions in
+    // Section 5.2.1).
+    void potrf(int64_t off, int64_t n, hipStream_t st)
     {
         if (n <= 0) return;
         if (n <= kTile) {
             note(tbs::launch_potrf_tile(dtype == TBS_F32, (int)n, at(off, off), lda, inv_of(off), info,
-                                        (int32_t)off, stream));
+                                        (int32_t)off, st));
             return;
         }
         const int64_t B = block_for(n);
         for (int64_t p0 = 0; p0 < n; p0 += B) {
             const int64_t nb = (B < n - p0) ? B : n - p0;
-            potrf(off + p0, nb);                                        // A[I0,I0] <- CHOL
+            potrf(off + p0, nb, st);                                    // A[I0,I0] <- CHOL
             const int64_t rest = n - p0 - nb, row0 = off + p0 + nb;
             if (rest <= 0) continue;
-            trsm(row0, rest, off + p0, nb);                             // A[I1,I0] <- TRSM
-            const tbs_status st = syrk_impl(false, dtype, rest, nb, -1.0, at(row0, off + p0), lda, 1.0,
-                                            at(row0, row0), lda, stream);  // A[I1,I1] <- TBS
-            if (st != TBS_OK) note(hipErrorUnknown);
+            trsm(row0, rest, off + p0, nb, st);                         // A[I1,I0] <- TRSM
+            note(syrk_impl(false, dtype, rest, nb, -1.0, at(row0, off + p0), lda, 1.0, at(row0, row0), lda,
+                           st));                                        // A[I1,I1] <- TBS
+        }
+    }
+
+    // Algorithm 5 at the top level with look-ahead.  The trailing update of panel p is split: first
+    // the block column of the next panel (its diagonal block by SYRK, the rows below by a product),
+    // then the rest.  As soon as the block column is up to date, the next panel's factorisation and
+    // solve (a long chain of small kernels) run on a second stream beside the rest of the update,
+    // which leaves a few compute units free for them.  The two touch disjoint parts of A: the rest of
+    // the update writes columns right of the next panel and reads the columns of panel p.
+    void potrf_top(int64_t N)
+    {
+        const int64_t B = block_for(N);
+        LookAhead* la = (N > 2 * B) ? look_ahead_for_device() : nullptr;
+        if (!la) {
+            potrf(0, N, stream);
+            return;
+        }
+        const bool f32 = dtype == TBS_F32;
+        int64_t nb = B;                                                 // width of panel p
+        potrf(0, nb, stream);
+        trsm(nb, N - nb, 0, nb, stream);
+        for (int64_t c0 = 0; c0 + nb < N;) {                            // c0: first column of panel p
+            const int64_t r0 = c0 + nb, rest = N - r0;                  // trailing matrix starts at r0
+            const int64_t nbn = (B < rest) ? B : rest;                  // width of panel p + 1
+            const int64_t below = rest - nbn;
+            note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, stream));
+            if (below > 0)
+                note(tbs::launch_gemm_nt(f32, below, nbn, nb, -1.0, at(r0 + nbn, c0), lda, at(r0, c0), lda, 1.0,
+                                         at(r0 + nbn, r0), lda, stream));
+            note(hipEventRecord(la->column_ready, stream));
+            if (below > 0)                                              // the long kernel first: the host
+                note(syrk_impl(false, dtype, below, nb, -1.0, at(r0 + nbn, c0), lda, 1.0, at(r0 + nbn, r0 + nbn),
+                               lda, stream, reserve_units));            // needs a while to queue the chain
+            note(hipStreamWaitEvent(la->panel, la->column_ready, 0));
+            potrf(r0, nbn, la->panel);
+            if (below > 0) trsm(r0 + nbn, below, r0, nbn, la->panel);
+            note(hipEventRecord(la->panel_done, la->panel));
+            note(hipStreamWaitEvent(stream, la->panel_done, 0));
+            c0 = r0;
+            nb = nbn;
         }
     }
 };
+
+int default_reserve_units()
+{
+    const char* e = std::getenv("TBS_POTRF_RESERVE");
+    if (e) {
+        const long v = std::atol(e);
+        if (v >= 0 && v <= 128) return (int)v;
+    }
+    return 24;
+}
 
 int64_t default_big_block()
 {
@@ -300,8 +377,9 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
     ctx.linv = static_cast<char*>(workspace) + kInfoBytes;
     ctx.stream = (hipStream_t)hip_stream;
     ctx.big_block = default_big_block();
+    ctx.reserve_units = default_reserve_units();
     ctx.note(tbs::launch_fill_i32(ctx.info, 0, 1, ctx.stream));
-    ctx.potrf(0, N);
+    ctx.potrf_top(N);
     if (ctx.err != hipSuccess) return TBS_EHIP;
     if (info_host) {
         int32_t info = 0;
