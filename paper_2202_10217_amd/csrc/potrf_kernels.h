@@ -6,11 +6,16 @@
 namespace tbs {
 
 // Factors the nb x nb (nb <= 64) diagonal tile at A in place (lower triangle; Algorithm 2 on one
-// tile) and writes the inverse of the factor, a 64 x 64 row-major lower triangular matrix (identity
-// beyond nb), to Linv.  A pivot that is not > 0 stores index0 + (its 0-based index) + 1 into *info
-// if *info is still 0, and leaves the rest of the tile unfactored.  All pointers: device.
-hipError_t launch_potrf_tile(bool f32, int nb, void* A, int64_t lda, void* Linv, int32_t* info,
-                             int32_t index0, hipStream_t stream);
+// tile).  A pivot that is not > 0 stores index0 + (its 0-based index) + 1 into *info if *info is
+// still 0; the columns from that one on are then unspecified.  All pointers: device.
+hipError_t launch_potrf_tile(bool f32, int nb, void* A, int64_t lda, int32_t* info, int32_t index0,
+                             hipStream_t stream);
+
+// X (m x nb, nb <= 64) <- X * L^{-T} by forward substitution, L the lower triangular nb x nb tile at
+// `L` (leading dimension ldl); X in place.  The column-scaling and update steps of Algorithm 2 for
+// the rows below a diagonal tile.
+hipError_t launch_trsm_tile(bool f32, int64_t m, int nb, const void* L, int64_t ldl, void* X, int64_t ldx,
+                            hipStream_t stream);
 
 // dst[0..n) = value, as a kernel (safe to record into a HIP graph, unlike a memset node).
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int n, hipStream_t stream);

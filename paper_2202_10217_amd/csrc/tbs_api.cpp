@@ -91,7 +91,7 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
 }
 
 // ---- Large Block Cholesky ------------------------------------------------------------------------
-constexpr size_t kInfoBytes = 256;                     // info word, padded to keep the rest aligned
+constexpr size_t kInfoBytes = 256;                     // the workspace holds the info word only
 
 // A second stream and two events per device for the look-ahead of Large Block Cholesky (created on
 // first use, default priority, kept until the process ends).
@@ -123,7 +123,6 @@ struct Lbc {
     size_t es;
     char* A;
     int64_t lda;
-    char* linv;          // one 64 x 64 inverse per diagonal tile
     int32_t* info;
     hipStream_t stream;  // the caller's stream
     int64_t big_block;   // panel width at the top level
@@ -131,7 +130,6 @@ struct Lbc {
     hipError_t err = hipSuccess;
 
     char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
-    char* inv_of(int64_t row) const { return linv + (size_t)(row / kTile) * kTile * kTile * es; }
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     void note(tbs_status st) { if (st != TBS_OK) note(hipErrorUnknown); }
 
@@ -145,14 +143,13 @@ struct Lbc {
 
     // X = A[row0 : row0+m, col0 : col0+nb]  <-  X * L^{-T},  L = A[col0 : col0+nb, col0 : col0+nb]
     // (the solve of Algorithm 5, "TRSM"): recursive on the column blocks of L; a 64-wide block is
-    // solved by multiplying with the inverse of its diagonal tile.
+    // solved by forward substitution against its diagonal tile.
     void trsm(int64_t row0, int64_t m, int64_t col0, int64_t nb, hipStream_t st)
     {
         if (m <= 0 || nb <= 0) return;
         const bool f32 = dtype == TBS_F32;
         if (nb <= kTile) {
-            note(tbs::launch_gemm_nt(f32, m, nb, nb, 1.0, at(row0, col0), lda, inv_of(col0), kTile, 0.0,
-                                     at(row0, col0), lda, st));
+            note(tbs::launch_trsm_tile(f32, m, (int)nb, at(col0, col0), lda, at(row0, col0), lda, st));
             return;
         }
         const int64_t nb1 = ((nb / kTile + 1) / 2) * kTile;
@@ -169,8 +166,7 @@ struct Lbc {
     {
         if (n <= 0) return;
         if (n <= kTile) {
-            note(tbs::launch_potrf_tile(dtype == TBS_F32, (int)n, at(off, off), lda, inv_of(off), info,
-                                        (int32_t)off, st));
+            note(tbs::launch_potrf_tile(dtype == TBS_F32, (int)n, at(off, off), lda, info, (int32_t)off, st));
             return;
         }
         const int64_t B = block_for(n);
@@ -233,7 +229,7 @@ int default_reserve_units()
         const long v = std::atol(e);
         if (v >= 0 && v <= 128) return (int)v;
     }
-    return 24;
+    return 48;
 }
 
 int64_t default_big_block()
@@ -349,8 +345,7 @@ tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32
 tbs_status tbs_potrf_lower_workspace(tbs_dtype dtype, int64_t N, size_t* bytes)
 {
     if (!dtype_ok(dtype) || N < 0 || N > kMaxN || !bytes) return TBS_EINVAL;
-    const size_t T = (size_t)((N + kTile - 1) / kTile);
-    *bytes = kInfoBytes + T * kTile * kTile * elem_size(dtype);
+    *bytes = kInfoBytes;
     return TBS_OK;
 }
 
@@ -374,7 +369,6 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
     ctx.A = static_cast<char*>(A);
     ctx.lda = lda;
     ctx.info = static_cast<int32_t*>(workspace);
-    ctx.linv = static_cast<char*>(workspace) + kInfoBytes;
     ctx.stream = (hipStream_t)hip_stream;
     ctx.big_block = default_big_block();
     ctx.reserve_units = default_reserve_units();

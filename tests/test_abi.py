@@ -66,7 +66,7 @@ def test_workspace_queries(lib):
     assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, 4096, 4096) == 0
     n64 = tb.tbs_potrf_lower_workspace(tb.TBS_F64, 1000)
     n32 = tb.tbs_potrf_lower_workspace(tb.TBS_F32, 1000)
-    assert n64 >= 16 * 64 * 64 * 8 and n32 >= 16 * 64 * 64 * 4 and n64 > n32
+    assert n64 >= 4 and n32 >= 4                              # at least the info word
     with pytest.raises(tb.TbsError):
         tb.tbs_potrf_lower_workspace(tb.TBS_F64, -1)
     with pytest.raises(tb.TbsError):
@@ -81,7 +81,7 @@ def test_potrf_argument_checks(lib):
     assert f(3, 8, fake, 8, fake, 1 << 20, ctypes.byref(info), None) == tb.TBS_EINVAL
     assert f(0, 8, fake, 7, fake, 1 << 20, ctypes.byref(info), None) == tb.TBS_EINVAL
     assert f(0, 8, None, 8, fake, 1 << 20, ctypes.byref(info), None) == tb.TBS_EINVAL
-    assert f(0, 8, fake, 8, fake, 8, ctypes.byref(info), None) == tb.TBS_EWORKSPACE
+    assert f(0, 8, fake, 8, fake, 2, ctypes.byref(info), None) == tb.TBS_EWORKSPACE
     assert f(0, 8, fake, 8, None, 0, ctypes.byref(info), None) == tb.TBS_EWORKSPACE
     assert f(0, 0, None, 1, None, 0, ctypes.byref(info), None) == tb.TBS_OK and info.value == 0
 
