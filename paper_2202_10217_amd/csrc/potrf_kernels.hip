@@ -11,90 +11,172 @@ namespace tbs {
 constexpr int kPT = 64;          // tile side
 constexpr int kPLd = kPT + 1;    // padded LDS row
 
-// One elimination step; K is a compile-time constant so that every register index is static.
-template <typename T, int K>
-__device__ __forceinline__ void tile_step(T (&s)[16], T* colL, T* pivot, int& fail, int i, int q, int perm_i)
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Per-type pieces: the 16x16x4 MFMA (lane l supplies A[l%16][l/16] and B[l/16][l%16]; row_of gives the
+// row of result register g), the hardware reciprocal square root, and a read of one lane's value.
+template <typename T> struct TileOps;
+template <> struct TileOps<double> {
+    typedef f64x4 acc_t;
+    static __device__ __forceinline__ acc_t mma(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row_of(int g, int lane) { return 4 * g + (lane >> 4); }
+    static __device__ __forceinline__ double rsq(double p) { return __builtin_amdgcn_rsq(p); }
+    static __device__ __forceinline__ double readlane(double v, int lane)
+    {
+        const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+        const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+        return __hiloint2double(hi, lo);
+    }
+};
+template <> struct TileOps<float> {
+    typedef f32x4 acc_t;
+    static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row_of(int g, int lane) { return 4 * (lane >> 4) + g; }
+    static __device__ __forceinline__ float rsq(float p) { return __builtin_amdgcn_rsqf(p); }
+    static __device__ __forceinline__ float readlane(float v, int lane)
+    {
+        return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+    }
+};
+
+// d = sqrt(p) and r ~ 1 / d for a pivot p > 0 (p is the same in every lane), without a branch.  The
+// hardware estimate of p^{-1/2} is refined by one coupled Newton step for (sqrt p, 1 / (2 sqrt p)) and
+// two residual steps on the root: d is the correctly rounded root whenever the root is representable
+// (so integer factors stay exact); r is good to a few ulps, which is all the corrected quotient in
+// PanelSteps needs.  Eight dependent operations instead of the several dozen of a library sqrt
+// followed by a division -- this sequence sits on the critical path of every column.  No rescaling is
+// done: for pivots below 2^-767 the residual p - d*d is no longer exact and d may be off by an ulp.
+template <typename T>
+__device__ __forceinline__ void sqrt_and_reciprocal(T p, T& d, T& r)
 {
-    constexpr int km = K >> 2, kq = K & 3;
-    T p = *pivot;
-    if (!(p > T(0))) {                                      // uniform: every thread reads the same p
-        if (fail < 0) fail = K;
-        p = T(1);                                           // keep going on finite numbers; the output
-    }                                                       // from column `fail` on is unspecified
-    // d = sqrt(p) and r = 1/d once per step; column entries are a/d computed as a*r followed by one
-    // residual correction (q + r*(a - q*d)), which returns the correctly rounded quotient whenever it
-    // is representable exactly -- in particular integer factors stay exact -- without a division
-    // sequence on the critical path of every step.
-    const T d = sqrt(p);
-    const T r = T(1) / d;
-    if (q == kq) {                                          // owners of column K
-        const T a = s[km];
-        const T q0 = a * r;
-        const T l = (i > K) ? fma(fma(-q0, d, a), r, q0) : d;
-        if (i >= K) s[km] = l;
-        colL[perm_i] = (i > K) ? l : T(0);
-    }
-    __syncthreads();
-    if ((i | 15) > K) {                                     // wavefronts whose 16 rows are all <= K idle
-        const T lik = colL[perm_i];
-#pragma unroll
-        for (int m = 0; m < 16; ++m)
-            if (m >= km) s[m] -= lik * colL[q * 16 + m];    // columns j > K (entries for j <= K are 0)
-    }
-    if (K + 1 < kPT && i == K + 1 && q == ((K + 1) & 3)) *pivot = s[((K + 1) >> 2) & 15];
-    __syncthreads();
+    const T y = TileOps<T>::rsq(p);
+    T g = p * y, h = T(0.5) * y;
+    const T e = fma(-h, g, T(0.5));
+    g = fma(g, e, g);
+    h = fma(h, e, h);
+    g = fma(fma(-g, g, p), h, g);
+    d = fma(fma(-g, g, p), h, g);
+    r = h + h;
 }
 
+// Columns 16 kb .. 16 kb + 15 of the tile for all rows from 16 kb down, by one wavefront: lane l holds
+// the 16 entries of row 16 kb + l in registers.  Step K is Algorithm 2's iteration for that column:
+// the pivot comes from lane K, every lane scales its entry of column K and updates its entries right
+// of it with the scaled entries of the rows K + 1 .. 15 (read from their lanes), so rows of the
+// diagonal block and rows below it run the same instructions and nothing goes through LDS.  The
+// sixteen steps are one straight line of code (a failed pivot is replaced by 1 with selects), so that
+// the updates of one step can fill the stalls of the next step's square root.
 template <typename T, int K>
-struct TileSteps {
-    static __device__ __forceinline__ void run(int nb, T (&s)[16], T* colL, T* pivot, int& fail, int i, int q,
-                                               int perm_i)
+struct PanelSteps {
+    static __device__ __forceinline__ void run(T (&s)[16], int lane, int col0, int& fail)
     {
-        if constexpr (K < kPT) {
-            if (K < nb) {                                   // uniform
-                tile_step<T, K>(s, colL, pivot, fail, i, q, perm_i);
-                TileSteps<T, K + 1>::run(nb, s, colL, pivot, fail, i, q, perm_i);
-            }
+        if constexpr (K < 16) {
+            T p = TileOps<T>::readlane(s[K], K);
+            const bool bad = !(p > T(0));
+            fail = (bad && fail < 0) ? col0 + K : fail;
+            p = bad ? T(1) : p;                             // keep going on finite numbers; the output
+            T d, r;                                         // from column `fail` on is unspecified
+            sqrt_and_reciprocal(p, d, r);
+            // a / d as a * r plus one residual correction: exact whenever the quotient is representable
+            const T a = s[K];
+            const T q0 = a * r;
+            const T l = (lane == K) ? d : fma(fma(-q0, d, a), r, q0);
+            s[K] = l;
+#pragma unroll
+            for (int j = K + 1; j < 16; ++j) s[j] -= l * TileOps<T>::readlane(l, j);
+            PanelSteps<T, K + 1>::run(s, lane, col0, fail);
         }
     }
 };
 
-// Thread (i, q) = (tid / 4, tid % 4) keeps the elements j = 4 m + q, m = 0..15, of row i of the
-// working matrix in registers for the whole factorisation.  A step needs one thing from other
-// threads, broadcast through LDS: the scaled column k of L (stored so that the 16 values a thread
-// needs are contiguous).  The elimination loop is unrolled completely (template recursion), so every
-// register index is a constant and a step only touches the columns that still change (j > k).
-//
-// The operations are those of Algorithm 2 in its order (pivot, scale column k, rank-1 update with the
-// scaled column), so integer-valued factors come out exactly.
+// Cholesky of one nb x nb tile (nb <= 64), one workgroup.  The tile sits in LDS (identity beyond nb).
+// For each block of 16 columns: wavefront 0 factors the block column (PanelSteps); then the four
+// wavefronts subtract its outer product from the 16 x 16 blocks to the right of it with MFMAs.
+// Within a block column the operations are those of Algorithm 2 in its order; across block columns
+// the 16 products of an update are summed by the MFMA before they are subtracted, which changes
+// rounding only (integer-valued factors still come out exactly).
 template <typename T>
 __global__ __launch_bounds__(256) void potrf_tile_kernel(int nb, T* __restrict__ A, int64_t lda, int32_t* info,
                                                          int32_t index0)
 {
-    __shared__ T colL[kPT];          // scaled column k, entry of row j at [(j % 4) * 16 + j / 4]; 0 for j <= k
-    __shared__ T pivot;              // S[k][k] entering step k
-    const int tid = threadIdx.x;
-    const int i = tid >> 2, q = tid & 3;
-    const int perm_i = (i & 3) * 16 + (i >> 2);
-    T s[16];
+    __shared__ T S[kPT * kPLd];
+    __shared__ int fail_sh;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    {
+        T v[16];
 #pragma unroll
-    for (int m = 0; m < 16; ++m) {
-        const int j = 4 * m + q;
-        const int ic = min(i, nb - 1), jc = min(j, ic);    // unconditional loads on clamped addresses
-        const T a = A[(int64_t)ic * lda + jc];
-        s[m] = (i < nb && j <= i) ? a : ((i == j) ? T(1) : T(0));   // identity padding beyond nb
+        for (int it = 0; it < 16; ++it) {                   // unconditional loads on clamped addresses, all
+            const int i = it * 4 + w, j = lane;             // in flight together; one row per wavefront
+            const int ic = min(i, nb - 1), jc = min(j, ic);
+            v[it] = A[(int64_t)ic * lda + jc];
+        }
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int i = it * 4 + w, j = lane;
+            S[i * kPLd + j] = (i < nb && j <= i) ? v[it] : ((i == j) ? T(1) : T(0));
+        }
     }
-    if (tid == 0) pivot = s[0];
-    int fail = -1;
+    if (tid == 0) fail_sh = -1;
     __syncthreads();
-    TileSteps<T, 0>::run(nb, s, colL, &pivot, fail, i, q, perm_i);
-    if (fail >= 0 && tid == 0 && *info == 0) *info = index0 + fail + 1;
-    // write back the columns that were finished (all of them when nothing failed)
-    const int ncol = (fail >= 0) ? fail : nb;
+    int fail = -1;
 #pragma unroll
-    for (int m = 0; m < 16; ++m) {
-        const int j = 4 * m + q;
-        if (i < nb && j <= i && j < ncol) A[(int64_t)i * lda + j] = s[m];
+    for (int kb = 0; kb < 4; ++kb) {
+        if (16 * kb < nb) {                                 // uniform
+            if (w == 0) {
+                const int row = min(16 * kb + lane, kPT - 1);
+                const bool live = 16 * kb + lane < kPT;
+                T s[16];
+#pragma unroll
+                for (int c = 0; c < 16; ++c) s[c] = S[row * kPLd + 16 * kb + c];
+                PanelSteps<T, 0>::run(s, lane, 16 * kb, fail);
+                if (live) {
+#pragma unroll
+                    for (int c = 0; c < 16; ++c) S[row * kPLd + 16 * kb + c] = s[c];
+                }
+            }
+            __syncthreads();
+            if (kb < 3) {
+                int idx = 0;
+#pragma unroll
+                for (int I = kb + 1; I < 4; ++I)
+#pragma unroll
+                    for (int J = kb + 1; J <= I; ++J) {
+                        if ((idx++ & 3) == w) {             // uniform per wavefront
+                            typename TileOps<T>::acc_t acc;
+                            T* c = S + (16 * I) * kPLd + 16 * J + (lane & 15);
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) acc[g] = c[TileOps<T>::row_of(g, lane) * kPLd];
+                            const T* ra = S + (16 * I + (lane & 15)) * kPLd + 16 * kb + (lane >> 4);
+                            const T* rb = S + (16 * J + (lane & 15)) * kPLd + 16 * kb + (lane >> 4);
+#pragma unroll
+                            for (int k4 = 0; k4 < 4; ++k4) acc = TileOps<T>::mma(ra[4 * k4], -rb[4 * k4], acc);
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) c[TileOps<T>::row_of(g, lane) * kPLd] = acc[g];
+                        }
+                    }
+                __syncthreads();
+            }
+        }
+    }
+    if (tid == 0 && fail >= 0) {
+        fail_sh = fail;
+        if (*info == 0) *info = index0 + fail + 1;
+    }
+    __syncthreads();
+    // write back the columns that were finished (all of them when nothing failed)
+    const int failed = fail_sh;
+    const int ncol = (failed >= 0) ? failed : nb;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int i = it * 4 + w, j = lane;
+        if (i < nb && j <= i && j < ncol) A[(int64_t)i * lda + j] = S[i * kPLd + j];
     }
 }
 
