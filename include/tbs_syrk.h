@@ -105,11 +105,13 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
 
 /* Expands the plan into its work list, with the very index arithmetic the kernels use.
  * Item t occupies items[t*8 .. t*8+7]:  [0] kind (0 triangle block, 1 rectangle, 2 diagonal tile,
- * 3 empty), [1] number of row-side tile rows, [2] number of column-side tile rows, [3..7] tile-row
- * ids, -1 = unused (triangle block: the members of R in zone order in [3..6]; rectangle: column
- * side in [3..5], row side in [6..7]; diagonal tile: [3]).  A rectangle updates the tiles (r, q) of
- * its row x column product with q < r only.  The plan depends on N and, for small N, on M (which
- * sets how finely the tail of the list is cut so that all compute units finish together).  `capacity` counts items; *n_items receives the number the plan has
+ * 3 empty, 4 rectangle with diagonal tiles), [1] number of row-side tile rows, [2] number of
+ * column-side tile rows, [3..7] tile-row ids, -1 = unused (triangle block: the members of R in zone
+ * order in [3..6]; rectangle: column side in [3..5], row side in [6..7]; diagonal tile: [3]).  A
+ * rectangle updates the tiles (r, q) of its row x column product with q < r only; kind 4 also
+ * updates the tiles with q = r (the part on and below the diagonal).  The plan depends on N and, for
+ * small N, on M (which sets how finely the tail of the list is cut so that all compute units finish
+ * together).  `capacity` counts items; *n_items receives the number the plan has
  * (call with items == NULL to size the buffer).  HOST pointers. */
 tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32_t square,
                                     int32_t* items, int64_t capacity, int64_t* n_items);

@@ -12,6 +12,7 @@
 //   * a diagonal tile: one panel, only the 10 of 16 sub-tiles on or below the diagonal.
 // Within a tile, wavefront w owns the 16-column strip w: 4 MFMA sub-tiles of 16 x 16 per tile.
 #include <hip/hip_runtime.h>
+#include <cstdlib>
 #include <stdint.h>
 
 #include <atomic>
@@ -262,43 +263,22 @@ struct AsmLoopArgs {
 };
 #include "syrk_asm_loops.inc"
 
-// C tile element update: C <- beta*C + alpha*acc (beta == 0: C is not read)
-template <typename T>
-__device__ __forceinline__ void store_subtile(const Mats<T>& m, int row0, int col,
-                                              const typename Cfg<T>::acc_t& acc, int lane, bool lower_only)
-{
-    T old[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int row = row0 + Cfg<T>::row_of(g, lane);
-        const bool ok = row < m.nr && col < m.nq && (!lower_only || col <= row);
-        old[g] = (ok && m.beta != T(0)) ? m.C[(int64_t)row * m.ldc + col] : T(0);
-    }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int row = row0 + Cfg<T>::row_of(g, lane);
-        const bool ok = row < m.nr && col < m.nq && (!lower_only || col <= row);
-        if (ok) {
-            const T v = m.alpha * acc[g];
-            m.C[(int64_t)row * m.ldc + col] = (m.beta != T(0)) ? m.beta * old[g] + v : v;
-        }
-    }
-}
-
 // The 16 elements of C that one lane holds of a 64 x 16 tile strip (4 row groups x 4 registers).
 template <typename T>
 struct TileStrip {
     T v[4][4];
     // CHECK: rows / columns beyond the matrix are skipped (ragged last tile)
+    // diag: the strip belongs to a diagonal tile; elements above the diagonal are not touched
     template <bool CHECK>
-    __device__ __forceinline__ void load(const Mats<T>& m, int row0, int col, int lane)
+    __device__ __forceinline__ void load(const Mats<T>& m, int row0, int col, int lane, bool diag)
     {
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int row = row0 + rb * 16 + Cfg<T>::row_of(g, lane);
-                v[rb][g] = (!CHECK || (row < m.nr && col < m.nq)) ? m.C[(int64_t)row * m.ldc + col] : T(0);
+                const bool ok = (!CHECK || (row < m.nr && col < m.nq)) && (!diag || col <= row);
+                v[rb][g] = ok ? m.C[(int64_t)row * m.ldc + col] : T(0);
             }
     }
 };
@@ -306,14 +286,15 @@ struct TileStrip {
 // Writes C <- beta*old + alpha*acc for one tile strip (beta == 0: old is not used).
 template <typename T, bool CHECK>
 __device__ __forceinline__ void store_strip(const Mats<T>& m, int row0, int col, int lane,
-                                            const typename Cfg<T>::acc_t (&acc)[4], const TileStrip<T>& old)
+                                            const typename Cfg<T>::acc_t (&acc)[4], const TileStrip<T>& old,
+                                            bool diag)
 {
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int row = row0 + rb * 16 + Cfg<T>::row_of(g, lane);
-            if (!CHECK || (row < m.nr && col < m.nq)) {
+            if ((!CHECK || (row < m.nr && col < m.nq)) && (!diag || col <= row)) {
                 const T v = m.alpha * acc[rb][g];
                 m.C[(int64_t)row * m.ldc + col] = (m.beta != T(0)) ? m.beta * old.v[rb][g] + v : v;
             }
@@ -333,7 +314,7 @@ __device__ __forceinline__ void store_strip(const Mats<T>& m, int row0, int col,
 //   with every access checked.
 template <typename T, class Shape, uint32_t SLOTS, bool FAST>
 __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
-                                           T* lds)
+                                           uint32_t dmask, T* lds)
 {
     constexpr int NP = Shape::NP;
     constexpr int KC = Cfg<T>::KC, KS = KC / 4, LDK = Cfg<T>::LDK;
@@ -458,7 +439,8 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
             for (int j = 0; j < Shape::NB; ++j)
                 if (slot_on<Shape>(SLOTS, i, j) && Shape::slot(i, j) == first && rd)
                     old[0].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
-                                                prow[Shape::b_panel(j)] * kTile + col16, lane);
+                                                prow[Shape::b_panel(j)] * kTile + col16, lane,
+                                                ((dmask >> first) & 1u) != 0);
 #pragma unroll
         for (int s = 0; s < Shape::NSLOT; ++s) {
             if (!((SLOTS >> s) & 1u)) continue;
@@ -475,7 +457,8 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                     for (int j = 0; j < Shape::NB; ++j)
                         if (Shape::active(i, j) && Shape::slot(i, j) == s2 && rd)
                             old[cur ^ 1].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
-                                                              prow[Shape::b_panel(j)] * kTile + col16, lane);
+                                                              prow[Shape::b_panel(j)] * kTile + col16, lane,
+                                                              ((dmask >> s2) & 1u) != 0);
             }
 #pragma unroll
             for (int i = 0; i < Shape::NA; ++i)
@@ -483,7 +466,8 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                 for (int j = 0; j < Shape::NB; ++j)
                     if (Shape::active(i, j) && Shape::slot(i, j) == s)
                         store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
-                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[s], old[cur]);
+                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[s], old[cur],
+                                              ((dmask >> s) & 1u) != 0);
             cur ^= 1;
         }
     } else {
@@ -497,8 +481,9 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                         const int row0 = prow[Shape::a_panel(i)] * kTile;
                         const int col = prow[Shape::b_panel(j)] * kTile + col16;
                         TileStrip<T> old;
-                        if (m.beta != T(0)) old.template load<true>(m, row0, col, lane);
-                        store_strip<T, true>(m, row0, col, lane, acc[s], old);
+                        const bool diag = ((dmask >> s) & 1u) != 0;
+                        if (m.beta != T(0)) old.template load<true>(m, row0, col, lane, diag);
+                        store_strip<T, true>(m, row0, col, lane, acc[s], old, diag);
                     }
                 }
     }
@@ -521,7 +506,7 @@ template <> struct FastSets<RectShape> {
 
 template <typename T, class Shape, int IDX>
 __device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
-                                         T* lds)
+                                         uint32_t dmask, T* lds)
 {
     if constexpr (IDX < FastSets<Shape>::N) {
         constexpr uint32_t SLOTS = FastSets<Shape>::set(IDX);
@@ -535,109 +520,44 @@ __device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Sha
                     whole = whole && (prow[p] + 1) * kTile <= nrows;
                 }
             if (!whole) return false;
-            block_body<T, Shape, SLOTS, true>(m, prow, pmask, lds);
+            block_body<T, Shape, SLOTS, true>(m, prow, pmask, dmask, lds);
             return true;
         }
-        return try_fast<T, Shape, IDX + 1>(m, prow, pmask, lds);
+        return try_fast<T, Shape, IDX + 1>(m, prow, pmask, dmask, lds);
     } else {
         return false;
     }
 }
 
+// with_diag: tiles (r, r) belong to the block (their part on and below the diagonal)
 template <typename T, class Shape>
-__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds)
+__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds, bool with_diag = false)
 {
     constexpr int NP = Shape::NP;
     int prow[NP];
 #pragma unroll
     for (int p = 0; p < NP; ++p) prow[p] = it.rows[p];      // -1: panel absent
-    uint32_t pmask = 0;
+    uint32_t pmask = 0, dmask = 0;
 #pragma unroll
     for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
         for (int j = 0; j < Shape::NB; ++j) {
             const int ar = prow[Shape::a_panel(i)], br = prow[Shape::b_panel(j)];
-            if (Shape::active(i, j) && ar >= 0 && br >= 0 && (!m.lower || br < ar))
-                pmask |= 1u << Shape::slot(i, j);
+            if (Shape::active(i, j) && ar >= 0 && br >= 0) {
+                if (!m.lower || br < ar) pmask |= 1u << Shape::slot(i, j);
+                if (m.lower && with_diag && br == ar) {
+                    pmask |= 1u << Shape::slot(i, j);
+                    dmask |= 1u << Shape::slot(i, j);
+                }
+            }
         }
     constexpr int KC = Cfg<T>::KC;
     const int64_t lim = (int64_t)1 << 32;                   // the assembly loop uses 32-bit byte offsets
     const bool fast_ok = m.M >= KC && m.M % KC == 0 && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
                          (int64_t)m.nr * m.ldr * (int64_t)sizeof(T) < lim &&
                          (int64_t)m.nq * m.ldq * (int64_t)sizeof(T) < lim;
-    if (fast_ok && try_fast<T, Shape, 0>(m, prow, pmask, lds)) return;
-    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false>(m, prow, pmask, lds);
-}
-
-// ---- diagonal tile: 10 sub-tiles on or below the diagonal, at most 3 per wavefront -------------
-template <typename T>
-__device__ __forceinline__ void run_diag(const Item& it, const Mats<T>& m, T* lds)
-{
-    constexpr int KC = Cfg<T>::KC, KS = KC / 4, LDK = Cfg<T>::LDK;
-    constexpr int kBufElems = kMaxPanels * kTile * LDK;
-    typedef typename Cfg<T>::acc_t acc_t;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // (row group, column group) of the wavefront's sub-tiles:
-    //   w0: (0,0) (1,0) (2,0)   w1: (1,1) (2,1) (3,1)   w2: (2,2) (3,2) (3,0)   w3: (3,3)
-    // Wavefront 3 repeats (3,3) in its two spare slots and drops those results: the loop is the same
-    // straight-line code for every wavefront.
-    const int nsub = (w == 3) ? 1 : 3;
-    int srow[3], scol[3];
-    srow[0] = w;
-    scol[0] = w;
-    srow[1] = (w >= 2) ? 3 : w + 1;
-    scol[1] = w;
-    srow[2] = (w >= 1) ? 3 : 2;
-    scol[2] = (w == 2) ? 0 : w;
-
-    acc_t acc[3];
-#pragma unroll
-    for (int s = 0; s < 3; ++s) acc[s] = acc_t{0, 0, 0, 0};
-
-    const int prow[1] = {it.rows[0]};
-    const T* const base[1] = {m.R};
-    const int64_t ld[1] = {m.ldr};
-    const int nrows[1] = {m.nr};
-    const bool aligned = vec_ok(m.R, m.ldr);
-    const int M = m.M;
-    const int nchunks = (M + KC - 1) / KC;
-    Stager<T, 1, 1u> st;
-    st.init(base, ld, nrows, prow, tid);
-    if (nchunks > 0) {
-        st.load_checked(M, 0, aligned && KC <= M, tid);
-        st.store(lds, tid);
-    }
-    __syncthreads();
-    const T* lane_base = lds + (lane & 15) * LDK + (lane >> 4);
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const bool more = ch + 1 < nchunks;
-        if (more) {
-            const int k0 = (ch + 1) * KC;
-            st.load_checked(M, k0, aligned && k0 + KC <= M, tid);
-        }
-        const T* buf = lane_base + (ch & 1) * kBufElems;
-        T a[KS][3], b[KS][3];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int s = 0; s < 3; ++s) {
-                a[ks][s] = buf[srow[s] * 16 * LDK + ks * 4];
-                b[ks][s] = buf[scol[s] * 16 * LDK + ks * 4];
-            }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int s = 0; s < 3; ++s) acc[s] = Cfg<T>::mfma(a[ks][s], b[ks][s], acc[s]);
-        if (more) st.store(lds + ((ch + 1) & 1) * kBufElems, tid);
-        __syncthreads();
-    }
-    const int t0 = it.rows[0] * kTile;
-#pragma unroll
-    for (int s = 0; s < 3; ++s)
-        if (s < nsub)
-            store_subtile<T>(m, t0 + srow[s] * 16, t0 + scol[s] * 16 + (lane & 15), acc[s], lane, true);
+    if (fast_ok && try_fast<T, Shape, 0>(m, prow, pmask, dmask, lds)) return;
+    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false>(m, prow, pmask, dmask, lds);
 }
 
 // ---- the kernels: workgroup -> block(s) -> code path ------------------------------------------
@@ -650,8 +570,13 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
         run_block<T, TriShape>(it, m, lds);
     } else if (it.kind == kRect) {
         run_block<T, RectShape>(it, m, lds);
-    } else if (it.kind == kDiag) {
-        run_diag<T>(it, m, lds);
+    } else if (it.kind == kRectDiag) {
+        run_block<T, RectShape>(it, m, lds, true);
+    } else if (it.kind == kDiag) {                          // a 1 x 1 rectangle on the diagonal
+        Item d = it;
+        d.rows[0] = it.rows[0];
+        d.rows[kRectCols] = it.rows[0];
+        run_block<T, RectShape>(d, m, lds, true);
     }
 }
 
@@ -673,6 +598,20 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, in
 // block, minus the cost of starting a workgroup for every block.  ctr[0] = next block, ctr[1] =
 // workgroups that have finished; the last one to finish sets both back to zero for the next launch
 // that uses the same pair.
+//
+// (A variant with one queue per accelerator die, each holding blocks that share panels of A, was
+// measured and dropped: the bytes fetched into the L2s did not change.  The workgroups of a die
+// drift apart by more chunks than its 4 MB L2 can hold for 28 blocks with six chunks in flight each.)
+#ifdef TBS_TRACE
+// measurement builds only: start and end time (100 MHz wall clock) and place of every block
+constexpr int kTraceItems = 1 << 16;
+__device__ unsigned long long g_trace[kTraceItems][3];
+extern "C" int tbs_trace_fetch(unsigned long long* host, int n_items)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 3 * (size_t)n_items);
+}
+#endif
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, int N, int M, T alpha,
                                                                        const T* __restrict__ A, int64_t lda,
@@ -688,7 +627,17 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
         __syncthreads();
         const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
         if (id >= plan.n_items) break;
+#ifdef TBS_TRACE
+        const unsigned long long t_start = wall_clock64();
+#endif
         run_item<T>(plan, id, m, reinterpret_cast<T*>(smem));
+#ifdef TBS_TRACE
+        if (threadIdx.x == 0 && id < kTraceItems) {
+            g_trace[id][0] = t_start;
+            g_trace[id][1] = wall_clock64();
+            g_trace[id][2] = (unsigned long long)blockIdx.x << 8;
+        }
+#endif
     }
     if (threadIdx.x == 0) {
         __threadfence();

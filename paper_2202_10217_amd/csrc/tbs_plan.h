@@ -8,7 +8,10 @@
 //   the l_L = T_L - k c_L last tile rows are covered by rectangular blocks, and each of the k
 //   diagonal zones (c_L tile rows) becomes a zone of level L+1;  if c_L < k-1 the zone is a base
 //   zone: one triangle block on its consecutive rows when it has at most k of them, rectangular
-//   blocks otherwise.  Diagonal tiles are never part of a block: they form one list of their own.
+//   blocks otherwise.  Diagonal tiles: the rectangular blocks that cover a triangular region (a base
+//   zone, the triangle of the last l_L tile rows) take the diagonal tiles of that region with them
+//   (item kind kRectDiag); a plan whose base zones are triangle blocks lists all diagonal tiles
+//   separately instead (kDiag).
 //
 // The descriptor is small enough to be a kernel argument; every workgroup turns its index into
 // its block with tbs_decode().  The host uses the same function to expand, count and check plans,
@@ -32,13 +35,15 @@ constexpr int kRectRows = 2;     // rectangular block: at most 2 x 3 tiles
 constexpr int kRectCols = 3;
 constexpr int kMaxPanels = 5;    // panels of A a block can stage (k, or kRectRows + kRectCols)
 
-enum ItemKind : int32_t { kTri = 0, kRect = 1, kDiag = 2, kEmpty = 3 };
+// kRect: tiles (r, q) of the block's rows x columns with q < r.  kRectDiag: q <= r, where of a tile
+// (r, r) only the part on and below the diagonal belongs to the block.
+enum ItemKind : int32_t { kTri = 0, kRect = 1, kDiag = 2, kEmpty = 3, kRectDiag = 4 };
 
 enum SegKind : int32_t {
     kSegTri = 0,       // c^2 triangle blocks in each zone of a level
     kSegTriBase = 1,   // one triangle block on the consecutive rows of each base zone
     kSegRect = 2,      // grid of rectangular blocks inside each zone of a level
-    kSegDiag = 3       // all diagonal tiles
+    kSegDiag = 3       // all diagonal tiles (only in plans whose rectangles do not carry them)
 };
 
 struct Seg {
@@ -50,6 +55,7 @@ struct Seg {
     int32_t c0, c1;    // kSegRect: tile columns [c0, c1) relative to the zone
     int32_t nI, nJ;    // kSegRect: blocks per zone along rows / columns
     int32_t mr, nc;    // kSegRect: block shape in tiles
+    int32_t diag;      // kSegRect: 1 = the columns reach the diagonal and tiles (r, r) belong to the blocks
 };
 
 struct Plan {
@@ -123,8 +129,8 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
         const int32_t rb = (ra + sg.mr < sg.r1) ? ra + sg.mr : sg.r1;
         const int32_t ca = sg.c0 + J * sg.nc;
         const int32_t cb = (ca + sg.nc < sg.c1) ? ca + sg.nc : sg.c1;
-        if (ca >= rb - 1) return;                  // no tile strictly below the diagonal: empty
-        it.kind = kRect;
+        if (ca > rb - 1 - (sg.diag ? 0 : 1)) return;   // no tile on the wanted side of the diagonal: empty
+        it.kind = sg.diag ? kRectDiag : kRect;
         it.ncol = cb - ca;
         it.nrow = rb - ra;
         for (int32_t q = 0; q < kRectCols; ++q)

@@ -23,10 +23,11 @@ int32_t choose_c(int32_t upper, int32_t k)
 namespace {
 
 Seg rect_seg(int32_t level, int64_t nz, int32_t r0, int32_t r1, int32_t c0, int32_t c1, int32_t mr,
-             int32_t nc)
+             int32_t nc, bool diag = false)
 {
     Seg s{};
     s.kind = kSegRect;
+    s.diag = diag ? 1 : 0;
     s.level = level;
     s.r0 = r0; s.r1 = r1; s.c0 = c0; s.c1 = c1;
     s.mr = mr; s.nc = nc;
@@ -42,20 +43,31 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
 {
     if (T < 0 || T > (1 << 15)) return false;
     if (tune.mr < 1 || tune.mr > kRectRows || tune.nc < 1 || tune.nc > kRectCols) return false;
+    if (tune.mr_deep < 0 || tune.mr_deep > kRectRows || tune.nc_deep < 0 || tune.nc_deep > kRectCols) return false;
     Plan p{};
     p.k = kK;
     p.T = T;
     std::vector<Seg> tri, rect, base;
-    const int32_t k = p.k, mr = tune.mr, nc = tune.nc;
+    const int32_t k = p.k;
+    // rectangles that cover a triangular region take its diagonal tiles along, unless base zones are
+    // triangle blocks (which cannot): then every diagonal tile is an item of its own
+    const bool with_diag = !tune.tri_base;
     {
         int32_t level = 0, Tl = T;
         int64_t nz = 1;
         for (;;) {
+            const int32_t mr = tune.mr, nc = tune.nc;       // rectangles left of a zone
+            // rectangles of a triangular region: their own shape, one tile row high when they carry
+            // the diagonal tiles (a block that straddles the diagonal then lacks only trailing
+            // tiles, which every code path handles at full speed)
+            const bool own = tune.mr_deep > 0 && tune.nc_deep > 0;
+            const int32_t mrt = with_diag ? 1 : (own ? tune.mr_deep : tune.mr);
+            const int32_t nct = own ? tune.nc_deep : tune.nc;
             const int32_t c = choose_c(Tl / k, k);
             const bool room = level < kMaxLevels - 1 && level < tune.tri_levels &&
                               (int)(tri.size() + rect.size()) + 3 < kMaxSegs - 2;
             if (c < k - 1 || !room) {                       // base zones (c too small)
-                if (Tl >= 2) {
+                if (Tl >= (with_diag ? 1 : 2)) {
                     if (Tl <= k && tune.tri_base) {
                         Seg s{};
                         s.kind = kSegTriBase;
@@ -64,7 +76,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
                         s.count = (int32_t)nz;
                         base.push_back(s);
                     } else {
-                        rect.push_back(rect_seg(level, nz, 0, Tl, 0, Tl - 1, mr, nc));
+                        rect.push_back(rect_seg(level, nz, 0, Tl, 0, with_diag ? Tl : Tl - 1, mrt, nct, with_diag));
                     }
                 }
                 break;
@@ -78,7 +90,8 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
             const int32_t done = k * c, l = Tl - done;
             if (l > 0) {                                    // the last l tile rows
                 rect.push_back(rect_seg(level, nz, done, Tl, 0, done, mr, nc));
-                if (l >= 2) rect.push_back(rect_seg(level, nz, done, Tl, done, Tl - 1, mr, nc));
+                if (l >= (with_diag ? 1 : 2))
+                    rect.push_back(rect_seg(level, nz, done, Tl, done, with_diag ? Tl : Tl - 1, mrt, nct, with_diag));
             }
             nz *= k;
             Tl = c;
@@ -105,7 +118,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
     std::stable_sort(all.begin(), all.end(),
                      [&](const Seg& a, const Seg& b) { return tiles_of(a) > tiles_of(b); });
     for (const Seg& s : all) push(s);
-    if (T > 0) {
+    if (T > 0 && !with_diag) {
         Seg d{};
         d.kind = kSegDiag;
         d.count = T;
@@ -128,13 +141,15 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
         double tiles = 0.0;
         if (it.kind == kTri) {
             tiles = 0.5 * it.nrow * (it.nrow - 1);
-        } else if (it.kind == kRect) {
+        } else if (it.kind == kRect || it.kind == kRectDiag) {
             for (int r = 0; r < kRectRows; ++r)
                 for (int q = 0; q < kRectCols; ++q)
-                    if (it.rows[kRectCols + r] >= 0 && it.rows[q] >= 0 && it.rows[q] < it.rows[kRectCols + r])
+                    if (it.rows[kRectCols + r] >= 0 && it.rows[q] >= 0 &&
+                        (it.rows[q] < it.rows[kRectCols + r] ||
+                         (it.kind == kRectDiag && it.rows[q] == it.rows[kRectCols + r])))
                         tiles += 1.0;
         } else if (it.kind == kDiag) {
-            tiles = 10.0 / 16.0;
+            tiles = 1.0;                                    // computed as a whole tile
         } else {
             continue;                                       // empty block: exits at once
         }
@@ -156,16 +171,18 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
     if (per_unit > 200.0 || T < 2) return true;
     double best = simulate_makespan(*out, ncu, overhead_tiles);
-    const int32_t shapes[4][2] = {{2, 3}, {1, 3}, {1, 2}, {1, 1}};
+    const int32_t shapes[5][2] = {{2, 3}, {2, 2}, {1, 3}, {1, 2}, {1, 1}};
     for (int32_t levels = kMaxLevels; levels >= 0; levels = (levels == kMaxLevels) ? 2 : levels - 1) {
         for (const auto& sh : shapes) {
-            const PlanTuning tune{levels, sh[0], sh[1], levels == kMaxLevels && sh[0] == 2};
-            Plan cand;
-            if (!build_plan(T, tune, &cand)) continue;
-            const double span = simulate_makespan(cand, ncu, overhead_tiles);
-            if (span < best * 0.98) {                       // prefer the coarser plan on near ties
-                best = span;
-                *out = cand;
+            for (int32_t nct = kRectCols; nct >= 1; --nct) {    // triangular regions: 1 x nct blocks
+                const PlanTuning tune{levels, sh[0], sh[1], false, 1, nct};
+                Plan cand;
+                if (!build_plan(T, tune, &cand)) continue;
+                const double span = simulate_makespan(cand, ncu, overhead_tiles);
+                if (span < best * 0.98) {                   // prefer the coarser plan on near ties
+                    best = span;
+                    *out = cand;
+                }
             }
         }
     }
@@ -190,10 +207,14 @@ void plan_stats(const Plan& p, int64_t N, int64_t M, PlanStats* st)
             if (it.kind == kTri) {
                 ++r.n_tri;
                 for (int32_t u = 0; u < it.nrow; ++u) a += panel_rows(it.rows[u]);
-            } else if (it.kind == kRect) {
+            } else if (it.kind == kRect || it.kind == kRectDiag) {
                 ++r.n_rect;
                 for (int32_t u = 0; u < kMaxPanels; ++u)
                     if (it.rows[u] >= 0) a += panel_rows(it.rows[u]);
+                if (it.kind == kRectDiag)
+                    for (int32_t q = 0; q < kRectCols; ++q)
+                        for (int32_t rr = 0; rr < kRectRows; ++rr)
+                            if (it.rows[q] >= 0 && it.rows[q] == it.rows[kRectCols + rr]) ++r.n_diag;
             } else if (it.kind == kDiag) {
                 ++r.n_diag;
                 a += panel_rows(it.rows[0]);

@@ -15,6 +15,8 @@ struct PlanTuning {
     int32_t tri_levels;      // levels that use triangle blocks (0: none, i.e. rectangles only)
     int32_t mr, nc;          // rectangular block: mr x nc tiles, mr <= kRectRows, nc <= kRectCols
     bool tri_base;           // base zones of <= k tile rows become one triangle block
+    int32_t mr_deep = 0, nc_deep = 0;   // shape of the rectangles of triangular regions (0: as mr, nc);
+                                        // one tile row high whenever they carry the diagonal tiles
 };
 
 // Plan for a matrix of T tile rows with the given tuning.  Returns false when T is out of range for

@@ -12,7 +12,7 @@ from oracle import tbs_schedule as ts
 from paper_2202_10217_amd import binding as tb
 
 B, K = 64, 4
-KIND_TRI, KIND_RECT, KIND_DIAG, KIND_EMPTY = 0, 1, 2, 3
+KIND_TRI, KIND_RECT, KIND_DIAG, KIND_EMPTY, KIND_RECTDIAG = 0, 1, 2, 3, 4
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -33,14 +33,14 @@ def _tiles_of(items):
                 for v in range(u):
                     assert R[u] > R[v]                     # zone order is increasing row order
                     yield R[u], R[v]
-        elif kind == KIND_RECT:
+        elif kind in (KIND_RECT, KIND_RECTDIAG):
             cols = [r for r in rows[:3] if r >= 0]
             rws = [r for r in rows[3:5] if r >= 0]
             assert len(cols) == ncol and len(rws) == nrow and nrow >= 1 and ncol >= 1
             produced = 0
             for r in rws:
                 for q in cols:
-                    if q < r:
+                    if q < r or (q == r and kind == KIND_RECTDIAG):   # the second kind carries diagonal tiles
                         produced += 1
                         yield r, q
             assert produced > 0                             # an item flagged rectangle is never empty
