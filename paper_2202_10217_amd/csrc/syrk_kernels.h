@@ -14,11 +14,10 @@ namespace tbs {
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
                        int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, hipStream_t stream);
 
-// C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, all row-major device matrices.  C may alias
-// R when n <= 192 and every workgroup's rows of R are only its own rows of C (the in-place
-// triangular solve by an inverted diagonal block): a workgroup reads all it needs before it writes.
+// C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, all row-major device matrices that do not
+// overlap.  `units`: compute units the launch can expect to have (sets the block shape).
 hipError_t launch_gemm_nt(bool f32, int64_t m, int64_t n, int64_t K, double alpha, const void* R,
                           int64_t ldr, const void* Q, int64_t ldq, double beta, void* C, int64_t ldc,
-                          hipStream_t stream);
+                          int units, hipStream_t stream);
 
 }  // namespace tbs

@@ -654,11 +654,13 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
 constexpr int kCounterPairs = 64;
 __device__ unsigned int g_syrk_counters[kCounterPairs][2];
 
-// C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, rectangular blocks of 2 x 3 tiles.
+// C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, rectangular blocks of mr x nc tiles
+// (mr <= 2, nc <= 3), one workgroup per block.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_cols, int K, T alpha,
                                                            const T* R, int64_t ldr, const T* Q,
-                                                           int64_t ldq, T beta, T* C, int64_t ldc, int nJ)
+                                                           int64_t ldq, T beta, T* C, int64_t ldc, int nJ,
+                                                           int mr, int nc)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
     T* lds = reinterpret_cast<T*>(smem);
@@ -670,13 +672,13 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
     it.ncol = 0;
 #pragma unroll
     for (int q = 0; q < kRectCols; ++q) {
-        const int t = J * kRectCols + q;
-        it.rows[q] = (t < Tn) ? t : -1;
+        const int t = J * nc + q;
+        it.rows[q] = (q < nc && t < Tn) ? t : -1;
     }
 #pragma unroll
     for (int r = 0; r < kRectRows; ++r) {
-        const int t = I * kRectRows + r;
-        it.rows[kRectCols + r] = (t < Tm) ? t : -1;
+        const int t = I * mr + r;
+        it.rows[kRectCols + r] = (r < mr && t < Tm) ? t : -1;
     }
     const Mats<T> m = {R, ldr, m_rows, Q, ldq, n_cols, C, ldc, K, alpha, beta, false};
     run_block<T, RectShape>(it, m, lds);
@@ -723,25 +725,44 @@ hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double 
                : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, stream);
 }
 
+// The block shape is the one with the shortest estimated time on `units` compute units: rounds of
+// blocks, each costing its tiles (K columns at one unit's share of the MFMA peak) plus the fixed
+// cost of a block.  A product with few blocks per unit is cut finer so that the last round is full.
 template <typename T>
 static hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const void* R, int64_t ldr,
-                                const void* Q, int64_t ldq, double beta, void* C, int64_t ldc,
+                                const void* Q, int64_t ldq, double beta, void* C, int64_t ldc, int units,
                                 hipStream_t stream)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     const int Tm = (int)((m + kTile - 1) / kTile), Tn = (int)((n + kTile - 1) / kTile);
-    const int nI = (Tm + kRectRows - 1) / kRectRows, nJ = (Tn + kRectCols - 1) / kRectCols;
+    const double tile_us = (double)K * (sizeof(T) == 4 ? 0.01334 : 0.02668), fixed_us = 15.0;
+    const int shapes[5][2] = {{2, 3}, {2, 2}, {1, 3}, {1, 2}, {1, 1}};
+    int mr = 2, nc = 3;
+    double best = 0.0;
+    if (units < 1) units = 1;
+    for (const auto& sh : shapes) {
+        const int64_t blocks = (int64_t)((Tm + sh[0] - 1) / sh[0]) * ((Tn + sh[1] - 1) / sh[1]);
+        const int64_t rounds = (blocks + units - 1) / units;
+        const double t = (double)rounds * (sh[0] * sh[1] * tile_us + fixed_us);
+        if (best == 0.0 || t < best * 0.97) {               // prefer the larger block on near ties
+            best = t;
+            mr = sh[0];
+            nc = sh[1];
+        }
+    }
+    const int nI = (Tm + mr - 1) / mr, nJ = (Tn + nc - 1) / nc;
     hipLaunchKernelGGL(gemm_nt_kernel<T>, dim3((unsigned)(nI * nJ)), dim3(kThreads), 0, stream, (int)m,
-                       (int)n, (int)K, (T)alpha, (const T*)R, ldr, (const T*)Q, ldq, (T)beta, (T*)C, ldc, nJ);
+                       (int)n, (int)K, (T)alpha, (const T*)R, ldr, (const T*)Q, ldq, (T)beta, (T*)C, ldc, nJ, mr,
+                       nc);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm_nt(bool f32, int64_t m, int64_t n, int64_t K, double alpha, const void* R,
                           int64_t ldr, const void* Q, int64_t ldq, double beta, void* C, int64_t ldc,
-                          hipStream_t stream)
+                          int units, hipStream_t stream)
 {
-    return f32 ? launch_gemm_t<float>(m, n, K, alpha, R, ldr, Q, ldq, beta, C, ldc, stream)
-               : launch_gemm_t<double>(m, n, K, alpha, R, ldr, Q, ldq, beta, C, ldc, stream);
+    return f32 ? launch_gemm_t<float>(m, n, K, alpha, R, ldr, Q, ldq, beta, C, ldc, units, stream)
+               : launch_gemm_t<double>(m, n, K, alpha, R, ldr, Q, ldq, beta, C, ldc, units, stream);
 }
 
 }  // namespace tbs

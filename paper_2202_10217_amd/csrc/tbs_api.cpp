@@ -171,7 +171,7 @@ struct Lbc {
         const int64_t nb1 = ((nb / kTile + 1) / 2) * kTile;
         trsm(row0, m, col0, nb1, st);
         note(tbs::launch_gemm_nt(f32, m, nb - nb1, nb1, -1.0, at(row0, col0), lda, at(col0 + nb1, col0), lda,
-                                 1.0, at(row0, col0 + nb1), lda, st));
+                                 1.0, at(row0, col0 + nb1), lda, compute_units(), st));
         trsm(row0, m, col0 + nb1, nb - nb1, st);
     }
 
@@ -222,7 +222,7 @@ struct Lbc {
             note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, stream));
             if (below > 0)
                 note(tbs::launch_gemm_nt(f32, below, nbn, nb, -1.0, at(r0 + nbn, c0), lda, at(r0, c0), lda, 1.0,
-                                         at(r0 + nbn, r0), lda, stream));
+                                         at(r0 + nbn, r0), lda, compute_units(), stream));
             note(hipEventRecord(la->column_ready, stream));
             if (below > 0)                                              // the long kernel first: the host
                 note(syrk_impl(false, dtype, below, nb, -1.0, at(r0 + nbn, c0), lda, 1.0, at(r0 + nbn, r0 + nbn),
