@@ -17,6 +17,11 @@ hipError_t launch_potrf_tile(bool f32, int nb, void* A, int64_t lda, int32_t* in
 hipError_t launch_trsm_tile(bool f32, int64_t m, int nb, const void* L, int64_t ldl, void* X, int64_t ldx,
                             hipStream_t stream);
 
+// The same for a lower triangular block L of n <= 512 columns (n x n, leading dimension ldl): one launch,
+// every workgroup takes 32 rows of X through all tile columns.  Returns hipErrorInvalidValue for n > 512.
+hipError_t launch_trsm_panel(bool f32, int64_t m, int n, const void* L, int64_t ldl, void* X, int64_t ldx,
+                             hipStream_t stream);
+
 // dst[0..n) = value, as a kernel (safe to record into a HIP graph, unlike a memset node).
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int n, hipStream_t stream);
 

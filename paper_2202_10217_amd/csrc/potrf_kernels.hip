@@ -308,6 +308,159 @@ __global__ __launch_bounds__(256) void trsm_tile_kernel(int m, int nb, const T* 
         }
 }
 
+// ---- triangular solve with a lower triangular block of up to 512 columns -------------------------
+// X (m x n) <- X * L^{-T}, L the n x n lower triangular factor (n <= 512), in one launch: the rows of
+// X do not depend on each other, so a workgroup takes 32 of them through all tile columns by itself
+// (no ordering between workgroups, no intermediate kernel).  For tile column jt:
+//   the 32 x 64 tile X_jt is loaded into MFMA accumulators and the products X_kt * L[jt][kt]^T of the
+//   tile columns kt < jt already solved (kept in LDS; L comes straight from global memory in operand
+//   layout, it is shared by every workgroup and stays in L2) are subtracted;
+//   the result goes through LDS to the four-lanes-per-row layout of TrsmSteps, is solved against the
+//   diagonal tile L[jt][jt] by forward substitution, and is written to global memory and, as the
+//   operand of the later tile columns, back to LDS.
+// The operations on an element are those of Algorithm 2 for the rows below a diagonal block, except
+// that the products of 64 columns are summed by the MFMA before they are subtracted.
+#ifdef TBS_TRACE
+__device__ unsigned long long g_panel_trace[8][6];      // measurement builds: phase times of workgroup 0
+#define PANEL_MARK(slot) do { if (blockIdx.x == 0 && tid == 0) g_panel_trace[jt][slot] = wall_clock64(); } while (0)
+#else
+#define PANEL_MARK(slot) do { } while (0)
+#endif
+constexpr int kPR = 32;                                    // rows of X per workgroup
+constexpr int kMaxPanelTiles = 8;                          // n <= 512
+constexpr int kXsLd = kPT * (kMaxPanelTiles - 1) + 2;      // LDS row of solved tiles (padded)
+
+template <typename T>
+__global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* __restrict__ L, int64_t ldl,
+                                                         T* X, int64_t ldx)
+{
+    __shared__ __attribute__((aligned(16))) T Xs[kPR * kXsLd];   // solved tiles 0 .. nt-2; also the staging tile
+    __shared__ __attribute__((aligned(16))) T Lq[kPT * kLqLd];   // diagonal tile, as in trsm_tile_kernel
+    __shared__ T dg[kPT], rdg[kPT];
+    typedef typename TileOps<T>::acc_t acc_t;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * kPR;
+    const int nt = (n + kPT - 1) / kPT;
+    // this lane's elements of a tile of X in accumulator layout (wavefront w owns columns 16 w ..
+    // 16 w + 15 of a tile, both groups of 16 rows); requested one tile column ahead, before anything
+    // else of the iteration, so that the loads have the whole iteration to arrive
+    auto load_x = [&](int jt, T (&x)[2][4]) {
+        const int col = jt * kPT + 16 * w + (lane & 15);
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t row = row0 + 16 * rg + TileOps<T>::row_of(g, lane);
+                const T v = X[min(row, (int64_t)m - 1) * ldx + min(col, n - 1)];
+                x[rg][g] = (row < m && col < n) ? v : T(0);
+            }
+    };
+    T xin[2][4], xnext[2][4];
+    load_x(0, xin);
+    for (int jt = 0; jt < nt; ++jt) {
+        const int c0 = jt * kPT;
+        const int nbw = min(kPT, n - c0);
+        PANEL_MARK(0);
+        // requests to global memory, in the order in which their data is needed (they complete in
+        // order): the first operand values of L, the diagonal tile L[jt][jt] (written to LDS after the
+        // products), the next tile of X
+        const int col = c0 + 16 * w + (lane & 15);
+        const T* lp = L + (int64_t)min(col, n - 1) * ldl + (lane >> 4);   // row `col` of L, this lane's k offset
+        const bool lrow_ok = col < n;
+        T bcur[16], bnxt[16];
+#pragma unroll
+        for (int s4 = 0; s4 < 16; ++s4) bcur[s4] = lp[(jt > 0) ? 4 * s4 : 0];
+        T lv[16];
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int k = it * 4 + w, j = lane;
+            const int kc = min(k, nbw - 1), jc = min(j, kc);
+            lv[it] = L[(int64_t)(c0 + kc) * ldl + c0 + jc];
+        }
+        const int dc = min(lane, nbw - 1);
+        const T dv = L[(int64_t)(c0 + dc) * ldl + c0 + dc];
+        load_x(min(jt + 1, nt - 1), xnext);
+        acc_t acc[2];
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) acc[rg][g] = xin[rg][g];
+        const T* xa = Xs + (lane & 15) * kXsLd + (lane >> 4);
+        // per tile column kt: the operand values of L for kt + 1 are requested from global memory and
+        // all operand values of X for kt are read from LDS before the 32 MFMAs of kt are issued
+        for (int kt = 0; kt < jt; ++kt) {
+            T a0[16], a1[16];
+#pragma unroll
+            for (int s4 = 0; s4 < 16; ++s4) {
+                a0[s4] = xa[kt * kPT + 4 * s4];
+                a1[s4] = xa[16 * kXsLd + kt * kPT + 4 * s4];
+            }
+            const int ktn = (kt + 1 < jt) ? kt + 1 : kt;    // last round: a harmless repeat
+#pragma unroll
+            for (int s4 = 0; s4 < 16; ++s4) bnxt[s4] = lp[ktn * kPT + 4 * s4];
+            T bneg[16];
+#pragma unroll
+            for (int s4 = 0; s4 < 16; ++s4) bneg[s4] = lrow_ok ? -bcur[s4] : T(0);
+            __builtin_amdgcn_sched_barrier(0);              // nothing of the next round moves up into
+#pragma unroll                                              // the MFMAs: it would wait for the loads
+            for (int s4 = 0; s4 < 16; ++s4) {
+                acc[0] = TileOps<T>::mma(a0[s4], bneg[s4], acc[0]);
+                acc[1] = TileOps<T>::mma(a1[s4], bneg[s4], acc[1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s4 = 0; s4 < 16; ++s4) bcur[s4] = bnxt[s4];
+        }
+        PANEL_MARK(1);
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) xin[rg][g] = xnext[rg][g];
+        // staging tile: the place of X_jt among the solved tiles; the last tile column is no operand
+        // of anything, it borrows place 0 once every wavefront is done with the solved tiles
+        const int place = (jt < nt - 1) ? jt : 0;
+        if (jt == nt - 1 && nt > 1) __syncthreads();
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                Xs[(16 * rg + TileOps<T>::row_of(g, lane)) * kXsLd + place * kPT + 16 * w + (lane & 15)] = acc[rg][g];
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int k = it * 4 + w, j = lane;
+            Lq[j * kLqLd + lq_perm(k)] = (k < nbw && j < k) ? lv[it] : T(0);
+        }
+        if (tid < kPT) {
+            const T d = (tid < nbw) ? dv : T(1);
+            dg[tid] = d;
+            rdg[tid] = T(1) / d;
+        }
+        __syncthreads();
+        PANEL_MARK(2);
+        if (tid < 4 * kPR) {                                // two wavefronts: four lanes per row
+            const int i = tid >> 2, q = tid & 3;
+            T* br = Xs + i * kXsLd + place * kPT;
+            T b[1][16], cur[16];
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                b[0][c] = br[8 * (c >> 1) + 2 * q + (c & 1)];
+                cur[c] = Lq[q * 16 + c];
+            }
+            TrsmSteps<T, 1, 0>::run(b, cur, dg[0], rdg[0], Lq, dg, rdg, q);
+            PANEL_MARK(3);
+            const int64_t row = row0 + i;
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                const int cc = 8 * (c >> 1) + 2 * q + (c & 1);
+                br[cc] = b[0][c];
+                if (row < m && c0 + cc < n) X[row * ldx + c0 + cc] = b[0][c];
+            }
+        }
+        __syncthreads();
+        PANEL_MARK(4);
+    }
+}
+
 __global__ void fill_i32_kernel(int32_t* dst, int32_t value, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -356,6 +509,21 @@ hipError_t launch_trsm_tile(bool f32, int64_t m, int nb, const void* L, int64_t 
         launch_trsm_typed<float>(m, nb, L, ldl, X, ldx, stream);
     else
         launch_trsm_typed<double>(m, nb, L, ldl, X, ldx, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_trsm_panel(bool f32, int64_t m, int n, const void* L, int64_t ldl, void* X, int64_t ldx,
+                             hipStream_t stream)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    if (n > kPT * kMaxPanelTiles) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((m + kPR - 1) / kPR);
+    if (f32)
+        hipLaunchKernelGGL(trsm_panel_kernel<float>, dim3(grid), dim3(256), 0, stream, (int)m, n, (const float*)L,
+                           ldl, (float*)X, ldx);
+    else
+        hipLaunchKernelGGL(trsm_panel_kernel<double>, dim3(grid), dim3(256), 0, stream, (int)m, n,
+                           (const double*)L, ldl, (double*)X, ldx);
     return hipGetLastError();
 }
 

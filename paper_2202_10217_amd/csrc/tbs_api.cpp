@@ -143,6 +143,11 @@ struct Lbc {
     hipStream_t stream;  // the caller's stream
     int64_t big_block;   // panel width at the top level
     int reserve_units;   // compute units the trailing update leaves to the panel stream
+    // A block of up to 512 columns and at most this many rows is solved by one launch (32 rows per
+    // workgroup, no kernel boundaries between its tile columns: the short chain that the last panels
+    // need); a taller one by the recursion below, whose products run as full-size blocks and make
+    // better use of the few compute units the panel stream has next to a long trailing update.
+    int64_t fused_trsm_rows = 6144;
     hipError_t err = hipSuccess;
 
     char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
@@ -158,14 +163,19 @@ struct Lbc {
     }
 
     // X = A[row0 : row0+m, col0 : col0+nb]  <-  X * L^{-T},  L = A[col0 : col0+nb, col0 : col0+nb]
-    // (the solve of Algorithm 5, "TRSM"): recursive on the column blocks of L; a 64-wide block is
-    // solved by forward substitution against its diagonal tile.
+    // (the solve of Algorithm 5, "TRSM"): a block of up to 64 columns is solved by forward substitution
+    // against its diagonal tile, one of up to 512 columns and not too many rows by the kernel that
+    // takes 32 rows through all tile columns; other blocks are split in two with a product in between.
     void trsm(int64_t row0, int64_t m, int64_t col0, int64_t nb, hipStream_t st)
     {
         if (m <= 0 || nb <= 0) return;
         const bool f32 = dtype == TBS_F32;
         if (nb <= kTile) {
             note(tbs::launch_trsm_tile(f32, m, (int)nb, at(col0, col0), lda, at(row0, col0), lda, st));
+            return;
+        }
+        if (nb <= 512 && m <= fused_trsm_rows) {
+            note(tbs::launch_trsm_panel(f32, m, (int)nb, at(col0, col0), lda, at(row0, col0), lda, st));
             return;
         }
         const int64_t nb1 = ((nb / kTile + 1) / 2) * kTile;
@@ -393,6 +403,10 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
     ctx.stream = (hipStream_t)hip_stream;
     ctx.big_block = default_big_block();
     ctx.reserve_units = default_reserve_units();
+    if (const char* e = std::getenv("TBS_POTRF_FUSED_ROWS")) {
+        const long v = std::atol(e);
+        if (v >= 0) ctx.fused_trsm_rows = v;
+    }
     ctx.note(tbs::launch_fill_i32(ctx.info, 0, 1, ctx.stream));
     ctx.potrf_top(N);
     if (ctx.err != hipSuccess) return TBS_EHIP;
