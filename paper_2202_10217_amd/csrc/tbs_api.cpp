@@ -148,6 +148,7 @@ struct Lbc {
     // need); a taller one by the recursion below, whose products run as full-size blocks and make
     // better use of the few compute units the panel stream has next to a long trailing update.
     int64_t fused_trsm_rows = 6144;
+    int64_t wide_rows = 8192;   // trailing matrices at least this tall get double-width panels
     hipError_t err = hipSuccess;
 
     char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
@@ -222,12 +223,17 @@ struct Lbc {
             return;
         }
         const bool f32 = dtype == TBS_F32;
-        int64_t nb = B;                                                 // width of panel p
+        // panels are twice as wide while the trailing matrix is tall: its update then runs on longer
+        // blocks (less of their time is prologue and epilogue), and the wider panel still finishes in
+        // the shadow of that update
+        auto width_for = [&](int64_t rest) { return (rest >= wide_rows) ? 2 * B : B; };
+        int64_t nb = width_for(N);                                      // width of panel p
         potrf(0, nb, stream);
         trsm(nb, N - nb, 0, nb, stream);
         for (int64_t c0 = 0; c0 + nb < N;) {                            // c0: first column of panel p
             const int64_t r0 = c0 + nb, rest = N - r0;                  // trailing matrix starts at r0
-            const int64_t nbn = (B < rest) ? B : rest;                  // width of panel p + 1
+            const int64_t wn = width_for(rest);
+            const int64_t nbn = (wn < rest) ? wn : rest;                // width of panel p + 1
             const int64_t below = rest - nbn;
             note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, stream));
             if (below > 0)
@@ -403,6 +409,10 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
     ctx.stream = (hipStream_t)hip_stream;
     ctx.big_block = default_big_block();
     ctx.reserve_units = default_reserve_units();
+    if (const char* e = std::getenv("TBS_POTRF_WIDE_ROWS")) {
+        const long v = std::atol(e);
+        if (v > 0) ctx.wide_rows = v;
+    }
     if (const char* e = std::getenv("TBS_POTRF_FUSED_ROWS")) {
         const long v = std::atol(e);
         if (v >= 0) ctx.fused_trsm_rows = v;
