@@ -251,6 +251,21 @@ __device__ __forceinline__ void mfma_step(const Operands<T, Shape, SLOTS>& op,
             }
 }
 
+#ifdef TBS_TRACE
+// measurement builds only: summed time (100 MHz ticks) inside the chunk loop [0], inside the epilogue
+// [1], number of blocks [2]
+__device__ unsigned long long g_phase[4];
+extern "C" int tbs_phase_fetch(unsigned long long* host, int reset)
+{
+    int e = (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 4);
+    if (reset) {
+        unsigned long long z[4] = {0, 0, 0, 0};
+        e |= (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z));
+    }
+    return e;
+}
+#endif
+
 // ---- the main loop in assembly (generated) -----------------------------------------------------
 struct AsmLoopArgs {
     uint32_t ada[8];        // LDS byte address of the lane's row-side operand piece for k-step j
@@ -324,6 +339,9 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     typedef typename Cfg<T>::acc_t acc_t;
     typedef Operands<T, Shape, SLOTS> Ops;
     const int tid = threadIdx.x;
+#ifdef TBS_TRACE
+    unsigned long long phase_mark = 0;
+#endif
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
@@ -388,7 +406,17 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                 go[q++] = (uint32_t)(row * ld[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
             }
         }
+#ifdef TBS_TRACE
+        const unsigned long long t_loop0 = wall_clock64();
+#endif
         AsmLoop<T, Shape, SLOTS>::run(acc, g, go);
+#ifdef TBS_TRACE
+        if (tid == 0) {
+            phase_mark = wall_clock64();
+            atomicAdd(&g_phase[0], phase_mark - t_loop0);
+            atomicAdd(&g_phase[2], 1ull);
+        }
+#endif
     } else {
       if (nchunks > 0) {
         const bool aligned = vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq);
@@ -421,55 +449,32 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
       }
     }
 
-    // Epilogue.  Every load of a tile strip is issued before any store of it, and (branch-free case)
-    // the loads of the next strip before the stores of the current one: the C traffic of a block is
-    // a handful of overlapped round trips, not one per sub-tile.
+    // Epilogue.
     const int col16 = w * 16 + (lane & 15);
     if constexpr (FAST) {
-        TileStrip<T> old[2];
-        int first = -1;
-#pragma unroll
-        for (int s = 0; s < Shape::NSLOT; ++s)
-            if (first < 0 && ((SLOTS >> s) & 1u)) first = s;
-        int cur = 0;
+        // all old values of the block are requested at once (the operand registers of the loop are
+        // free now), then every strip is computed and stored
+        TileStrip<T> old[Shape::NSLOT];
         const bool rd = m.beta != T(0);
 #pragma unroll
         for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
             for (int j = 0; j < Shape::NB; ++j)
-                if (slot_on<Shape>(SLOTS, i, j) && Shape::slot(i, j) == first && rd)
-                    old[0].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
-                                                prow[Shape::b_panel(j)] * kTile + col16, lane,
-                                                ((dmask >> first) & 1u) != 0);
+                if (slot_on<Shape>(SLOTS, i, j) && rd)
+                    old[Shape::slot(i, j)].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
+                                                                prow[Shape::b_panel(j)] * kTile + col16, lane,
+                                                                ((dmask >> Shape::slot(i, j)) & 1u) != 0);
 #pragma unroll
-        for (int s = 0; s < Shape::NSLOT; ++s) {
-            if (!((SLOTS >> s) & 1u)) continue;
-            // the next active slot, if any: prefetch its old values
+        for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
-            for (int s2 = s + 1; s2 < Shape::NSLOT; ++s2) {
-                bool is_next = ((SLOTS >> s2) & 1u) != 0;
-#pragma unroll
-                for (int s3 = s + 1; s3 < s2; ++s3) is_next = is_next && !((SLOTS >> s3) & 1u);
-                if (!is_next) continue;
-#pragma unroll
-                for (int i = 0; i < Shape::NA; ++i)
-#pragma unroll
-                    for (int j = 0; j < Shape::NB; ++j)
-                        if (Shape::active(i, j) && Shape::slot(i, j) == s2 && rd)
-                            old[cur ^ 1].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
-                                                              prow[Shape::b_panel(j)] * kTile + col16, lane,
-                                                              ((dmask >> s2) & 1u) != 0);
-            }
-#pragma unroll
-            for (int i = 0; i < Shape::NA; ++i)
-#pragma unroll
-                for (int j = 0; j < Shape::NB; ++j)
-                    if (Shape::active(i, j) && Shape::slot(i, j) == s)
-                        store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
-                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[s], old[cur],
-                                              ((dmask >> s) & 1u) != 0);
-            cur ^= 1;
-        }
+            for (int j = 0; j < Shape::NB; ++j)
+                if (slot_on<Shape>(SLOTS, i, j))
+                    store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
+                                          prow[Shape::b_panel(j)] * kTile + col16, lane, acc[Shape::slot(i, j)],
+                                          old[Shape::slot(i, j)], ((dmask >> Shape::slot(i, j)) & 1u) != 0);
+#ifdef TBS_TRACE
+        if (tid == 0) atomicAdd(&g_phase[1], wall_clock64() - phase_mark);
+#endif
     } else {
 #pragma unroll
         for (int i = 0; i < Shape::NA; ++i)
