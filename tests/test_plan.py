@@ -73,6 +73,27 @@ def test_every_lower_tile_exactly_once(N, M, square):
         assert info["n_tri_blocks"] == 0
 
 
+TUNINGS = ["0,2,3,0", "0,1,1,0", "1,2,3,0,1,3", "1,1,3,0,1,2", "1,2,2,0,1,1", "2,1,2,0,1,3", "10,2,3,1",
+           "10,2,3,0,1,3", "10,1,1,0,1,1", "2,2,3,1"]
+
+
+@pytest.mark.parametrize("idx", range(len(TUNINGS)))
+def test_every_pinned_tuning_covers_the_triangle_exactly_once(idx, monkeypatch):
+    # the planner's candidates (levels, rectangle shape, base zones as triangle blocks, shape inside
+    # triangular regions), pinned through the environment; a size of its own per tuning, because the
+    # library keeps one plan per size
+    monkeypatch.setenv("TBS_PLAN_TUNING", TUNINGS[idx])
+    for N in (4096 + 64 * (idx + 1), 1500 + 64 * idx, 64 * (idx + 1) - 5):
+        items = tb.tbs_syrk_lower_enumerate(tb.TBS_F32, N, 777)
+        T = (N + B - 1) // B
+        count = np.zeros((T, T), dtype=np.int32)
+        for r, q in _tiles_of(items):
+            assert 0 <= q <= r < T
+            count[r, q] += 1
+        assert (count[np.tril_indices(T)] == 1).all() and count.sum() == T * (T + 1) // 2
+        assert tb.tbs_syrk_lower_query(tb.TBS_F32, N, 777)["n_diag_tiles"] == T
+
+
 def test_empty_matrix():
     assert len(tb.tbs_syrk_lower_enumerate(tb.TBS_F64, 0, 5)) == 0
 

@@ -96,6 +96,46 @@ def test_fp32(tb):
     assert oracle.llt_residual(L, S0.astype(np.float64)) <= 2e-6
 
 
+def _probe_check(L, S0):
+    """||L (L^T x) - A x|| / (||A||_F ||x||) for a few random x, and exact rows of L L^T for a sample of
+    rows, in float64 on the host (the N^3/3-flop residual is too slow there at these sizes)."""
+    N = S0.shape[0]
+    x = inputs.normal_matrix(N, 4, seed=17)
+    r = L @ (L.T @ x) - S0 @ x
+    nrmA = np.linalg.norm(S0)
+    rel = np.linalg.norm(r, axis=0) / (nrmA * np.linalg.norm(x, axis=0))
+    assert rel.max() <= 1e-13
+    rows = np.unique(np.clip(np.array([0, 1, 63, 64, 511, 512, 513, 5000, 6143, 6144, 6500, 8191, 8192, 12345,
+                                       N - 2, N - 1]), 0, N - 1))
+    rec = L[rows] @ L.T                                      # rows of L L^T
+    for rr, line in zip(rows, rec):
+        assert np.abs(line[:rr + 1] - S0[rr, :rr + 1]).max() <= 1e-13 * nrmA / np.sqrt(N) * 50
+
+
+@pytest.mark.parametrize("N", [7000, 9001])
+def test_ragged_sizes_beyond_the_one_launch_solve(tb, N):
+    # N is no multiple of the tile, and the first panels have more rows below them than the one-launch
+    # triangular solve takes, so both forms of the solve, the look-ahead and (9001) a double-width panel
+    # all meet ragged edges here
+    S0 = inputs.spd_diag_dominant(N, seed=5)
+    info, out = _factor(tb, S0)
+    assert info == 0
+    assert np.array_equal(out[np.triu_indices(N, 1)], S0[np.triu_indices(N, 1)])   # upper part untouched
+    _probe_check(np.tril(out), S0)
+
+
+def test_exact_integer_factor_with_look_ahead(tb):
+    # the same bit-exact recovery as above at a size that uses the second stream and the tall solve
+    N = 6600
+    rng = np.random.default_rng(11)
+    G = np.tril(rng.integers(-1, 2, size=(N, N))).astype(np.float64)
+    np.fill_diagonal(G, rng.integers(1, 3, size=N))
+    S = G @ G.T
+    info, out = _factor(tb, S)
+    assert info == 0
+    assert np.array_equal(np.tril(out), G)
+
+
 def test_config4_n16384_probe_residual(tb):
     # full size: the N^3/3-flop residual is too slow on the host; use random probes
     #   ||L (L^T x) - A x|| / (||A||_F ||x||)  for a few x, and the exact columns of L L^T for a
@@ -108,12 +148,4 @@ def test_config4_n16384_probe_residual(tb):
     assert info == 0
     L = np.tril(d.cpu().numpy())
     del d
-    x = inputs.normal_matrix(N, 4, seed=17)
-    r = L @ (L.T @ x) - S0 @ x
-    nrmA = np.linalg.norm(S0)
-    rel = np.linalg.norm(r, axis=0) / (nrmA * np.linalg.norm(x, axis=0))
-    assert rel.max() <= 1e-13
-    rows = np.array([0, 1, 63, 64, 511, 512, 513, 5000, 8191, 8192, 12345, N - 2, N - 1])
-    rec = L[rows] @ L.T                                      # rows of L L^T
-    for rr, line in zip(rows, rec):
-        assert np.abs(line[:rr + 1] - S0[rr, :rr + 1]).max() <= 1e-13 * nrmA / np.sqrt(N) * 50
+    _probe_check(L, S0)
