@@ -13,8 +13,18 @@ OUT = os.path.join(OUT_DIR, "libtbs_syrk.so")
 SOURCES = ["syrk_kernels.hip", "potrf_kernels.hip", "tbs_planner.cpp", "tbs_api.cpp"]
 
 
+def generate_loops() -> str:
+    """Writes csrc/syrk_asm_loops.inc from csrc/gen_asm_loops.py (the main loops of the SYRK kernels)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("gen_asm_loops", os.path.join(CSRC, "gen_asm_loops.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod.main()
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(OUT_DIR, exist_ok=True)
+    generate_loops()
     cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            # no packed fp32 arithmetic: some forms have given wrong results on this hardware
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

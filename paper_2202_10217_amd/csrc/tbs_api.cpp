@@ -115,7 +115,8 @@ struct LookAhead {
     hipStream_t panel = nullptr;
     hipEvent_t column_ready = nullptr, panel_done = nullptr;
     bool ok = false;
-};
+    std::mutex enqueue;     // held while a call records into the stream and the events: calls from
+};                          // several host threads then simply follow each other on the panel stream
 
 LookAhead* look_ahead_for_device()
 {
@@ -222,6 +223,7 @@ struct Lbc {
             potrf(0, N, stream);
             return;
         }
+        std::lock_guard<std::mutex> lock(la->enqueue);
         const bool f32 = dtype == TBS_F32;
         // panels are twice as wide while the trailing matrix is tall: its update then runs on longer
         // blocks (less of their time is prologue and epilogue), and the wider panel still finishes in
