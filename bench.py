@@ -19,16 +19,19 @@ PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3}       # MI355X dense matrix peaks, TFL
 # HBM bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel
 # of known size); filled in from the summaries under profiles/ for the workloads measured there.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/tbs_syrk_persistent_kernel_f64_n4096_m4096.md: 1.853e9 read + 6.72e7 written
-    ("syrk_n4096_m4096_f64", False): 1.920e9,
+    # profiles/tbs_syrk_persistent_kernel_f64_n4096_m4096.md: 1.796e9 read + 6.72e7 written
+    ("syrk_n4096_m4096_f64", False): 1.864e9,
 }
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # defaults: the clock of the chip rises for some tens of milliseconds after load sets in (the first
+    # launches after an idle phase run at about 2.1 GHz, later ones faster), so the warm-up is long enough
+    # for the timed launches to see the steady state; a launch of the default workload takes 1.1 ms
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="syrk_n4096_m4096_f64")
     ap.add_argument("--shape", default=None, help="N,M,dtype: a SYRK shape outside the configuration list "
                     "(C <- C - A A^T, A iid N(0,1)/sqrt(M)), for kernel studies")
@@ -149,7 +152,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dname],
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS[dname], 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.square)),
-                     "kernel": "tbs_syrk_kernel", "kernel_ms": round(kern_ms, 4),
+                     "kernel": "tbs_syrk_persistent_kernel", "kernel_ms": round(kern_ms, 4),
                      "flops_per_launch": flops},
         "io_model": {"S_C_elems": info["S_C_elems"], "S_res_elems": info["S_res_elems"],
                      "A_bytes_plan": info["A_elems"] * es, "C_bytes_read": info["C_elems"] * es * (beta != 0),
