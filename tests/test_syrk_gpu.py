@@ -142,6 +142,37 @@ def test_leading_dimensions_and_unaligned_views(tb, dtype):
     assert (out[:, 0] == 7.0).all() and (out[:, N + 1:] == 7.0).all()
 
 
+def test_matrices_of_4_gib_or_more_use_64_bit_offsets(tb):
+    # the assembly loop addresses A with 32-bit byte offsets and is only used below 4 GiB; a matrix whose
+    # rows are spread over 4.6 GB (huge leading dimension, few columns) must take the other path and
+    # give the same bits on integer data
+    N, M, lda = 4096, 64, 140000
+    A = inputs.small_int_matrix(N, M, seed=21)
+    C0 = inputs.symmetric_uniform(N, seed=22, int_range=(-3, 3))
+    Cref = C0.copy()
+    oracle.syrk_lower(A, Cref, -1.0, 1.0)
+    big = torch.empty((N, lda), dtype=torch.float64, device="cuda")
+    big[:, :M] = _dev(A)
+    dC = _dev(C0)
+    tb.tbs_syrk_lower(big[:, :M], dC, -1.0, 1.0)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    del big
+    il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+    assert np.array_equal(out[il], Cref[il])
+    assert np.array_equal(out[iu], C0[iu])
+
+
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (-1.0, 1.0), (0.5, -2.0), (0.0, 3.0), (2.0, 1.0)])
+def test_alpha_beta_combinations(tb, alpha, beta):
+    N, M = 777, 208                                         # ragged last tile, 13 whole chunks
+    A = inputs.uniform_matrix(N, M, seed=31)
+    C0 = inputs.symmetric_uniform(N, seed=32)
+    Cg = _run(tb, A, C0, alpha, beta)
+    Cref, D = _reference(A, C0, alpha, beta)
+    _check(Cg, C0, Cref, D, np.float64)
+
+
 def test_square_baseline_parity(tb):
     N, M = 900, 120
     A = inputs.normal_matrix(N, M, seed=21)
