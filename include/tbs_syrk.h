@@ -81,10 +81,13 @@ tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double a
 typedef struct {
     int32_t k;                 /* side of a triangle block, in tile rows                         */
     int32_t b;                 /* tile side, in elements                                         */
-    int32_t c;                 /* top-level modulus of the cyclic family (0: no triangle blocks) */
+    int32_t c;                 /* top-level modulus of the indexing family (0: no triangle blocks) */
     int32_t l;                 /* top-level leftover tile rows, T - k*c                          */
     int32_t levels;            /* recursion levels that use triangle blocks                      */
     int32_t tile_rows;         /* T = ceil(N / b)                                                */
+    int32_t family;            /* top level: 0 = the cyclic family of Section 5.1.2; m > 0 = c is 2^m  */
+                               /* and f(0)=j, f(1)=i, f(2)=i^j, f(3)=i^(x j mod x^m+x+1)            */
+    int32_t reserved;          /* 0                                                              */
     int64_t n_items;           /* workgroups launched                                            */
     int64_t n_tri_blocks;      /* triangle blocks, all levels                                    */
     int64_t n_rect_blocks;     /* rectangular blocks (leftover rows, recursion base)             */

@@ -84,9 +84,46 @@ def choose_c(upper: int, k: int) -> int:
     return max(c, 0)
 
 
-def block_rows(i: int, j: int, c: int, k: int) -> List[int]:
+def poly_mul_mod(a: int, b: int, m: int) -> int:
+    """Product of two polynomials over GF(2) (bit t = coefficient of x^t) modulo x^m + x + 1."""
+    r = 0
+    while b:
+        if b & 1:
+            r ^= a
+        b >>= 1
+        a <<= 1
+        if a >> m:
+            a ^= (1 << m) | 3
+    return r
+
+
+def xor_f(i: int, j: int, u: int, c: int) -> int:
+    """An indexing family for c = 2^m that is not in the paper (its Section 5.1.2 gives the cyclic one,
+    which needs c odd for k >= 4): f(0) = j, f(u) = i XOR (j * a_u) for u > 0, with a_u = u - 1 read as a
+    polynomial over GF(2) and the product taken modulo x^m + x + 1.  It is valid by the definition of
+    Section 5.1.1 whenever the differences a_u XOR a_v are invertible modulo that polynomial; for
+    k <= 4 these are 1, x and x + 1, which always are (the polynomial has constant term 1 and an odd
+    number of terms).  Validity is checked by brute force in the tests, not taken from this argument."""
+    m = c.bit_length() - 1
+    assert c == 1 << m
+    return j if u == 0 else i ^ poly_mul_mod(j, u - 1, m)
+
+
+def choose_family(upper: int, k: int) -> Tuple[str, int]:
+    """The family and modulus for zones of `upper` = floor(rows / k) rows: the cyclic family with the
+    largest admissible c, or the XOR family with the largest power of two if that covers more rows."""
+    c = choose_c(upper, k)
+    if k <= 4 and upper >= 4:
+        c2 = 1 << (upper.bit_length() - 1)
+        if c2 > c and c2 >= k - 1:
+            return "xor", c2
+    return "cyclic", c
+
+
+def block_rows(i: int, j: int, c: int, k: int, family: str = "cyclic") -> List[int]:
     """R^{i,j} = { u*c + f^{i,j}(u) : 0 <= u < k } (Equation 1)."""
-    return [u * c + cyclic_f(i, j, u, c) for u in range(k)]
+    f = cyclic_f if family == "cyclic" else xor_f
+    return [u * c + f(i, j, u, c) for u in range(k)]
 
 
 # ----------------------------------------------------------------------------
@@ -144,11 +181,12 @@ def ooc_syrk_last_rows(A, C, rows_all: np.ndarray, first: int, s: int, alpha: fl
 
 
 def tbs_syrk(A: np.ndarray, C: np.ndarray, k: int, b: int = 1, s: int = None,
-             alpha: float = 1.0, io: IOCount = None, _rows=None, _level=0) -> IOCount:
+             alpha: float = 1.0, io: IOCount = None, _rows=None, _level=0, families: str = "cyclic") -> IOCount:
     """Algorithm 4 (b = 1) and its tiled form (b > 1): C[lower] += alpha * A A^T, in place.
 
     `s` is the side of the square blocks used where the paper calls OOC_SYRK
     (default: the side whose area equals the triangle block's, rounded down).
+    families = "cyclic": the paper's family at every level; "auto": choose_family() at every level.
     """
     if io is None:
         io = IOCount()
@@ -157,17 +195,17 @@ def tbs_syrk(A: np.ndarray, C: np.ndarray, k: int, b: int = 1, s: int = None,
     N = len(rows)
     if s is None:
         s = max(1, int(math.isqrt(b * b * k * (k - 1) // 2)))
-    c = choose_c(N // (k * b), k)
+    family, c = ("cyclic", choose_c(N // (k * b), k)) if families == "cyclic" else choose_family(N // (k * b), k)
     if c < k - 1:                               # c too small: square blocks only
         ooc_syrk(A, C, rows, s, alpha, io)
         return io
     covered = c * k * b
     ooc_syrk_last_rows(A, C, rows, covered, s, alpha, io)          # the last l rows
     for z in range(k):                                              # diagonal zones
-        tbs_syrk(A, C, k, b, s, alpha, io, rows[z * c * b:(z + 1) * c * b], _level + 1)
+        tbs_syrk(A, C, k, b, s, alpha, io, rows[z * c * b:(z + 1) * c * b], _level + 1, families)
     for i in range(c):                                              # all c^2 blocks
         for j in range(c):
-            R = block_rows(i, j, c, k)                              # tile rows within this zone
+            R = block_rows(i, j, c, k, family)                      # tile rows within this zone
             io.blocks.append((_level, int(rows[0]) // b, R))
             tiles = [rows[r * b:(r + 1) * b] for r in R]
             io.C += b * b * k * (k - 1) // 2                        # load C[TB(R)]

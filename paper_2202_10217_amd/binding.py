@@ -30,6 +30,7 @@ class TbsError(RuntimeError):
 class PlanInfo(ctypes.Structure):
     _fields_ = [("k", ctypes.c_int32), ("b", ctypes.c_int32), ("c", ctypes.c_int32), ("l", ctypes.c_int32),
                 ("levels", ctypes.c_int32), ("tile_rows", ctypes.c_int32),
+                ("family", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("n_items", ctypes.c_int64), ("n_tri_blocks", ctypes.c_int64),
                 ("n_rect_blocks", ctypes.c_int64), ("n_diag_tiles", ctypes.c_int64),
                 ("S_C_elems", ctypes.c_int64), ("S_res_elems", ctypes.c_int64),

@@ -60,11 +60,16 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M)
         // TBS_PLAN_TUNING="levels,rows,cols,base,zone_rows,zone_cols" pins the tuning the planner would
         // otherwise choose (for measurements; every tuning covers each tile exactly once)
         const char* pin = square ? nullptr : std::getenv("TBS_PLAN_TUNING");
+        // TBS_PLAN_FAMILY=cyclic: the paper's cyclic family only (no power-of-two moduli)
+        const char* famenv = std::getenv("TBS_PLAN_FAMILY");
+        const bool xor_family = !(famenv && famenv[0] == 'c');
         int lv = 0, mr = 0, nc = 0, base = 0, mrd = 0, ncd = 0;
         if (pin && std::sscanf(pin, "%d,%d,%d,%d,%d,%d", &lv, &mr, &nc, &base, &mrd, &ncd) >= 4 && lv >= 0 &&
             lv <= tbs::kMaxLevels && mr >= 1 && mr <= tbs::kRectRows && nc >= 1 && nc <= tbs::kRectCols) {
-            if (!tbs::build_plan(T, tbs::PlanTuning{lv, mr, nc, base != 0, mrd, ncd}, &p)) return nullptr;
-        } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p)) {
+            tbs::PlanTuning tune{lv, mr, nc, base != 0, mrd, ncd};
+            tune.xor_family = xor_family;
+            if (!tbs::build_plan(T, tune, &p)) return nullptr;
+        } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family)) {
             return nullptr;
         }
         it = cache.emplace(key, p).first;
@@ -340,6 +345,7 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
     r.levels = st.levels;
     r.c = st.levels > 0 ? plan->c[0] : 0;
     r.l = st.levels > 0 ? T - kK * plan->c[0] : T;
+    r.family = st.levels > 0 ? plan->fam[0] : 0;
     r.tile_rows = T;
     r.n_items = plan->n_items;
     r.n_tri_blocks = st.n_tri;

@@ -4,7 +4,10 @@
 //   level 0 is the whole matrix (T tile rows); a level with T_L tile rows per zone picks
 //   c_L = largest integer <= T_L / k coprime with every integer of [2, k-2] (Section 5.1.2);
 //   if c_L >= k-1 its c_L^2 triangle blocks R^{i,j} = { u c_L + f^{i,j}(u) : u < k }, with the
-//   cyclic family f(0) = j, f(u) = (i + j (u-1)) mod c_L, cover the k(k-1)/2 square zones,
+//   cyclic family f(0) = j, f(u) = (i + j (u-1)) mod c_L, cover the k(k-1)/2 square zones
+//   (where a power of two 2^m <= T_L / k exceeds that c_L, the level uses c_L = 2^m with the family
+//   f(0) = j, f(1) = i, f(2) = i XOR j, f(3) = i XOR (x j mod x^m + x + 1), which is valid by the same
+//   definition (Section 5.1.1) and leaves fewer tile rows over),
 //   the l_L = T_L - k c_L last tile rows are covered by rectangular blocks, and each of the k
 //   diagonal zones (c_L tile rows) becomes a zone of level L+1;  if c_L < k-1 the zone is a base
 //   zone: one triangle block on its consecutive rows when it has at most k of them, rectangular
@@ -64,6 +67,7 @@ struct Plan {
     int32_t nseg;
     int32_t n_items;
     int32_t c[kMaxLevels];      // modulus of each level that has triangle blocks
+    int32_t fam[kMaxLevels];    // 0: cyclic family; m > 0: the XOR family with c = 2^m
     Seg seg[kMaxSegs];
 };
 
@@ -107,11 +111,20 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
         it.kind = kTri;
         it.nrow = kK;
         it.rows[0] = base + j;
-        int32_t f = i;                              // f(1) = i, f(u+1) = f(u) + j mod c
-        for (int32_t u = 1; u < kK; ++u) {
-            it.rows[u] = base + u * c + f;
-            f += j;
-            if (f >= c) f -= c;
+        const int32_t m = p.fam[sg.level];
+        if (m == 0) {
+            int32_t f = i;                          // f(1) = i, f(u+1) = f(u) + j mod c
+            for (int32_t u = 1; u < kK; ++u) {
+                it.rows[u] = base + u * c + f;
+                f += j;
+                if (f >= c) f -= c;
+            }
+        } else {                                    // f(u) = i XOR (j * a_u), a = 0, 1, x
+            static_assert(kK == 4, "the XOR family is written out for k = 4");
+            const int32_t xj = ((j << 1) ^ ((j >> (m - 1)) ? 3 : 0)) & (c - 1);
+            it.rows[1] = base + c + i;
+            it.rows[2] = base + 2 * c + (i ^ j);
+            it.rows[3] = base + 3 * c + (i ^ xj);
         }
     } else if (sg.kind == kSegTriBase) {
         const int32_t base = zone_base(p, sg.level, t);

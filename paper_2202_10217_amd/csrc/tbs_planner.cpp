@@ -63,7 +63,15 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
             const bool own = tune.mr_deep > 0 && tune.nc_deep > 0;
             const int32_t mrt = with_diag ? 1 : (own ? tune.mr_deep : tune.mr);
             const int32_t nct = own ? tune.nc_deep : tune.nc;
-            const int32_t c = choose_c(Tl / k, k);
+            int32_t c = choose_c(Tl / k, k), fam = 0;
+            if (tune.xor_family && Tl / k >= 4) {
+                int32_t m = 0;
+                while ((2 << m) <= Tl / k) ++m;             // 2^m = largest power of two <= Tl / k
+                if ((1 << m) > c) {
+                    c = 1 << m;
+                    fam = m;
+                }
+            }
             const bool room = level < kMaxLevels - 1 && level < tune.tri_levels &&
                               (int)(tri.size() + rect.size()) + 3 < kMaxSegs - 2;
             if (c < k - 1 || !room) {                       // base zones (c too small)
@@ -82,6 +90,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
                 break;
             }
             p.c[level] = c;
+            p.fam[level] = fam;
             Seg s{};
             s.kind = kSegTri;
             s.level = level;
@@ -162,10 +171,11 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
     return end;
 }
 
-bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out)
+bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family)
 {
     if (square) return build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out);
-    const PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
+    PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
+    coarse.xor_family = xor_family;
     if (!build_plan(T, coarse, out)) return false;
     // with many blocks per compute unit the granularity of the tail does not matter
     const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
@@ -175,7 +185,8 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     for (int32_t levels = kMaxLevels; levels >= 0; levels = (levels == kMaxLevels) ? 2 : levels - 1) {
         for (const auto& sh : shapes) {
             for (int32_t nct = kRectCols; nct >= 1; --nct) {    // triangular regions: 1 x nct blocks
-                const PlanTuning tune{levels, sh[0], sh[1], false, 1, nct};
+                PlanTuning tune{levels, sh[0], sh[1], false, 1, nct};
+                tune.xor_family = xor_family;
                 Plan cand;
                 if (!build_plan(T, tune, &cand)) continue;
                 const double span = simulate_makespan(cand, ncu, overhead_tiles);

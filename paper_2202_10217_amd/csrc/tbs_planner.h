@@ -17,6 +17,7 @@ struct PlanTuning {
     bool tri_base;           // base zones of <= k tile rows become one triangle block
     int32_t mr_deep = 0, nc_deep = 0;   // shape of the rectangles of triangular regions (0: as mr, nc);
                                         // one tile row high whenever they carry the diagonal tiles
+    bool xor_family = true;  // levels may use c = 2^m with the XOR family where that covers more rows
 };
 
 // Plan for a matrix of T tile rows with the given tuning.  Returns false when T is out of range for
@@ -28,7 +29,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
 // few blocks, the candidates differ in how finely the diagonal zones and the last tile rows are cut,
 // and the one with the shortest simulated makespan on `ncu` compute units is taken (blocks are
 // dispatched in list order to the first free unit; a block costs its tiles plus `overhead_tiles`).
-bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out);
+bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family = true);
 
 // Makespan, in tile units, of dispatching the plan's blocks in order onto ncu units.
 double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles);

@@ -70,6 +70,70 @@ def test_blocks_partition_the_square_zones(c, k):
         assert r // c > r2 // c
 
 
+# ---- the XOR family for c = 2^m (not in the paper; valid by the definition of Section 5.1.1) -------
+
+def test_polynomial_product_against_hand_values():
+    # modulo x^3 + x + 1:  x * x^2 = x^3 = x + 1;  (x + 1)(x^2 + 1) = x^3 + x^2 + x + 1 = x^2
+    assert ts.poly_mul_mod(0b010, 0b100, 3) == 0b011
+    assert ts.poly_mul_mod(0b011, 0b101, 3) == 0b100
+    # modulo x^2 + x + 1 (the field of four elements): x * x = x + 1, x (x + 1) = 1
+    assert ts.poly_mul_mod(2, 2, 2) == 3 and ts.poly_mul_mod(2, 3, 2) == 1
+    for m in range(2, 7):
+        for a in range(1 << m):
+            assert ts.poly_mul_mod(a, 1, m) == a and ts.poly_mul_mod(a, 0, m) == 0
+            for b in range(1 << m):
+                assert ts.poly_mul_mod(a, b, m) == ts.poly_mul_mod(b, a, m) < (1 << m)
+
+
+@pytest.mark.parametrize("c", [4, 8, 16, 32, 64])
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_xor_family_is_valid_by_brute_force(c, k):
+    assert ts.is_valid_family(lambda i, j, u: ts.xor_f(i, j, u, c), c, k)
+    seen = set()
+    for i in range(c):
+        for j in range(c):
+            for pair in ts.triangle_block(ts.block_rows(i, j, c, k, "xor")):
+                assert pair not in seen
+                seen.add(pair)
+    assert len(seen) == c * c * k * (k - 1) // 2            # exactly the pairs in different zones
+    assert all(r // c > r2 // c for r, r2 in seen)
+
+
+def test_xor_family_anchor_points():
+    c = 16
+    assert [ts.xor_f(5, 9, u, c) for u in range(4)] == [9, 5, 5 ^ 9, 5 ^ ((9 << 1) ^ 0b10011) & 15]
+    assert ts.block_rows(0, 0, c, 4, "xor") == [0, 16, 32, 48]
+    assert ts.block_rows(3, 0, c, 4, "xor") == [0, 19, 35, 51]           # j = 0: every f(u > 0) is i
+
+
+def test_choose_family():
+    assert ts.choose_family(16, 4) == ("xor", 16) and ts.choose_family(15, 4) == ("cyclic", 15)
+    assert ts.choose_family(64, 4) == ("xor", 64) and ts.choose_family(63, 4) == ("cyclic", 63)
+    assert ts.choose_family(4, 4) == ("xor", 4) and ts.choose_family(5, 4) == ("cyclic", 5)
+    assert ts.choose_family(3, 4) == ("cyclic", 3) and ts.choose_family(0, 4) == ("cyclic", 0)
+    assert ts.choose_family(16, 8) == ("cyclic", 13)       # written out for k <= 4 only
+    for n in range(1, 200):
+        fam, c = ts.choose_family(n, 4)
+        assert c <= n and c >= ts.choose_c(n, 4)
+        if fam == "xor":
+            assert c & (c - 1) == 0 and c > ts.choose_c(n, 4)
+
+
+@pytest.mark.parametrize("N,M,b", [(16, 3, 1), (64, 4, 1), (67, 3, 1), (128, 2, 2), (256, 2, 1)])
+def test_tbs_with_the_xor_family_equals_algorithm_1(N, M, b):
+    A = inputs.small_int_matrix(N, M, seed=N + 3)
+    C0 = inputs.symmetric_uniform(N, seed=N + 4, int_range=(-5, 5))
+    C_ref = C0.copy()
+    oracle.syrk_lower(A, C_ref, 1.0, 1.0)
+    C = C0.copy()
+    io = ts.tbs_syrk(A, C, 4, b, families="auto")
+    il = np.tril_indices(N)
+    assert np.array_equal(C[il], C_ref[il])
+    assert io.C == N * (N + 1) // 2
+    fam, c = ts.choose_family(N // (4 * b), 4)
+    assert fam == "xor" and io.A_q1 == c * c * 4 * b * M
+
+
 def test_choose_c():
     assert ts.choose_c(16, 4) == 15 and ts.choose_c(15, 4) == 15
     assert ts.choose_c(64, 4) == 63 and ts.choose_c(128, 4) == 127

@@ -99,18 +99,20 @@ def test_empty_matrix():
 
 
 @pytest.mark.parametrize("N,M", [(768, 64), (4096, 4096), (4096, 32), (16384, 512), (12345, 100), (32768, 64)])
-def test_triangle_blocks_are_those_of_the_cyclic_family(N, M):
-    # the CPU replay of Algorithm 4 on a T x 1 problem with b = 1 lists the blocks of every level
+def test_triangle_blocks_are_those_of_the_indexing_family(N, M):
+    # the CPU replay of Algorithm 4 on a T x 1 problem with b = 1 lists the blocks of every level (with
+    # the library's rule for the family of a level: cyclic, or XOR where a power of two covers more rows)
     T = N // B                                              # full tiles only: the replay has no ragged edge
     items = tb.tbs_syrk_lower_enumerate(tb.TBS_F64, T * B, M)
-    io = ts.tbs_syrk(np.zeros((T, 1)), np.zeros((T, T)), K, 1)
+    io = ts.tbs_syrk(np.zeros((T, 1)), np.zeros((T, T)), K, 1, families="auto")
     want = {lv: sorted(tuple(off + r for r in R) for l2, off, R in io.blocks if l2 == lv)
             for lv in range(10)}
     all_want = set(sum(want.values(), []))
     lib_tri = [tuple(row[3:3 + K]) for row in items.tolist() if row[0] == KIND_TRI and row[1] == K]
     family = [R for R in lib_tri if _is_family_block(R)]
     info = tb.tbs_syrk_lower_query(tb.TBS_F64, T * B, M)
-    c = ts.choose_c(T // K, K)
+    fam, c = ts.choose_family(T // K, K)
+    assert (info["family"] > 0) == (fam == "xor") and (fam == "cyclic" or c == 1 << info["family"])
     # every family block of the library is one of the replay's; the library uses the levels 0 ..
     # levels-1 of the recursion completely (deeper zones may be cut into rectangles instead, which
     # is the library's choice for small matrices) 
@@ -139,7 +141,7 @@ def test_query_numbers_against_the_formulas():
     assert math.isclose(info["tiled_lead_elems"], ts.tiled_tbs_A_leading(N, M, K, B), rel_tol=1e-12)
     assert math.isclose(info["square_elems"], ts.square_A_volume(N, M, math.sqrt(S)), rel_tol=1e-12)
     assert info["C_elems"] == N * (N + 1) / 2
-    assert (info["c"], info["l"]) == (15, 4) and 1 <= info["levels"] <= 2
+    assert (info["c"], info["l"], info["family"]) == (16, 0, 4) and 1 <= info["levels"] <= 2
     # the triangle blocks alone stay under the tiled bound N^2 M / ((k-1) b); no schedule beats the
     # lower bound.  (At this size the library cuts the diagonal zones finely to keep all compute
     # units busy, which costs A traffic; the comparison with square blocks is made at a size where
