@@ -244,3 +244,40 @@ def test_config2_integer_exact_full_size(tb):
     for r, g, e in zip(rows, got, exact):
         assert np.array_equal(g[:r + 1], e[:r + 1].astype(np.float64))
         assert not g[r + 1:].any()
+
+
+def test_calls_on_several_streams_do_not_disturb_each_other(tb):
+    # persistent launches take their blocks through counters in device memory; launches that may run
+    # at the same time must not share a counter pair.  Three streams, several calls each, on integer
+    # data (any lost or doubled block shows as a wrong integer); a Cholesky on a fourth stream, which
+    # brings its own second stream and events, runs beside them.
+    N, M = 2304, 96
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    As = [inputs.small_int_matrix(N, M, seed=40 + i) for i in range(3)]
+    C0 = inputs.symmetric_uniform(N, seed=44, int_range=(-3, 3))
+    refs = []
+    for A in As:
+        R = C0.copy()
+        for _ in range(3):
+            oracle.syrk_lower(A, R, 1.0, 1.0)
+        refs.append(R)
+    n = 3000
+    rng = np.random.default_rng(5)
+    G = np.tril(rng.integers(-1, 2, size=(n, n))).astype(np.float64)
+    np.fill_diagonal(G, 1.0)
+    dS = _dev(G @ G.T)
+    dAs = [_dev(A) for A in As]
+    dCs = [_dev(C0) for _ in As]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for i in range(3):
+            with torch.cuda.stream(streams[i]):
+                tb.tbs_syrk_lower(dAs[i], dCs[i], 1.0, 1.0)
+        if rep == 0:
+            with torch.cuda.stream(streams[3]):
+                tb.tbs_potrf_lower(dS, want_info=False)
+    torch.cuda.synchronize()
+    il = np.tril_indices(N)
+    for i in range(3):
+        assert np.array_equal(dCs[i].cpu().numpy()[il], refs[i][il]), i
+    assert np.array_equal(np.tril(dS.cpu().numpy()), G)
