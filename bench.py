@@ -106,8 +106,18 @@ def main():
     dname = "f64" if A.dtype == np.float64 else "f32"
     dA = torch.from_numpy(A).cuda()
     dC = torch.from_numpy(C0).cuda()
-    fn = tb.tbs_syrk_lower_square if args.square else tb.tbs_syrk_lower
     flops = float(N) * float(N + 1) * float(M)
+    # the library's workspace (parts of blocks that are cut along the contraction dimension), allocated
+    # once, outside the timed region, as a caller in a loop would
+    code = tb.TBS_F64 if dname == "f64" else tb.TBS_F32
+    ws_bytes = 0 if args.square else tb.tbs_syrk_lower_workspace(code, N, M)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") if ws_bytes > 0 else False
+    if args.square:
+        def fn(a, c, al, be):
+            return tb.tbs_syrk_lower_square(a, c, al, be)
+    else:
+        def fn(a, c, al, be):
+            return tb.tbs_syrk_lower(a, c, al, be, workspace=ws)
 
     for _ in range(args.warmup):
         fn(dA, dC, alpha, beta)

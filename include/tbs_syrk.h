@@ -87,7 +87,7 @@ typedef struct {
     int32_t tile_rows;         /* T = ceil(N / b)                                                */
     int32_t family;            /* top level: 0 = the cyclic family of Section 5.1.2; m > 0 = c is 2^m  */
                                /* and f(0)=j, f(1)=i, f(2)=i^j, f(3)=i^(x j mod x^m+x+1)            */
-    int32_t reserved;          /* 0                                                              */
+    int32_t max_slices;        /* blocks are cut along the contraction dimension into at most this many parts */
     int64_t n_items;           /* workgroups launched                                            */
     int64_t n_tri_blocks;      /* triangle blocks, all levels                                    */
     int64_t n_rect_blocks;     /* rectangular blocks (leftover rows, recursion base)             */
@@ -100,21 +100,26 @@ typedef struct {
     double  tbs_bound_elems;   /* N^2 M / (sqrt(2) sqrt(S_C))  (corollary of Section 4.1)        */
     double  tiled_lead_elems;  /* N^2 M / ((k-1) b)            (Section 5.1.4)                   */
     double  square_elems;      /* N^2 M / sqrt(S_C)            (square blocks of equal area)     */
+    int64_t n_sliced_blocks;   /* blocks computed in parts (0: none, no workspace needed)        */
+    int64_t workspace_bytes;   /* what tbs_syrk_lower_workspace reports for this plan            */
 } tbs_plan_info;
 
-/* square != 0 describes the plan of tbs_syrk_lower_square. */
+/* square = 0: the plan of tbs_syrk_lower when it is given its workspace; 1: the plan of
+ * tbs_syrk_lower_square; 2: the plan of tbs_syrk_lower without a workspace. */
 tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t square,
                                 tbs_plan_info* out);
 
 /* Expands the plan into its work list, with the very index arithmetic the kernels use.
- * Item t occupies items[t*8 .. t*8+7]:  [0] kind (0 triangle block, 1 rectangle, 2 diagonal tile,
+ * Item t occupies items[t*10 .. t*10+9]:  [0] kind (0 triangle block, 1 rectangle, 2 diagonal tile,
  * 3 empty, 4 rectangle with diagonal tiles), [1] number of row-side tile rows, [2] number of
  * column-side tile rows, [3..7] tile-row ids, -1 = unused (triangle block: the members of R in zone
  * order in [3..6]; rectangle: column side in [3..5], row side in [6..7]; diagonal tile: [3]).  A
  * rectangle updates the tiles (r, q) of its row x column product with q < r only; kind 4 also
  * updates the tiles with q = r (the part on and below the diagonal).  The plan depends on N and, for
  * small N, on M (which sets how finely the tail of the list is cut so that all compute units finish
- * together).  `capacity` counts items; *n_items receives the number the plan has
+ * together).  [8], [9]: the item is part [8] of the [9] parts its block is cut into along the
+ * contraction dimension (0 of 1: a whole block); the parts of a block are consecutive items.
+ * `square` as for the query.  `capacity` counts items; *n_items receives the number the plan has
  * (call with items == NULL to size the buffer).  HOST pointers. */
 tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32_t square,
                                     int32_t* items, int64_t capacity, int64_t* n_items);

@@ -30,13 +30,14 @@ class TbsError(RuntimeError):
 class PlanInfo(ctypes.Structure):
     _fields_ = [("k", ctypes.c_int32), ("b", ctypes.c_int32), ("c", ctypes.c_int32), ("l", ctypes.c_int32),
                 ("levels", ctypes.c_int32), ("tile_rows", ctypes.c_int32),
-                ("family", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("family", ctypes.c_int32), ("max_slices", ctypes.c_int32),
                 ("n_items", ctypes.c_int64), ("n_tri_blocks", ctypes.c_int64),
                 ("n_rect_blocks", ctypes.c_int64), ("n_diag_tiles", ctypes.c_int64),
                 ("S_C_elems", ctypes.c_int64), ("S_res_elems", ctypes.c_int64),
                 ("A_elems", ctypes.c_double), ("A_elems_top", ctypes.c_double), ("C_elems", ctypes.c_double),
                 ("tbs_bound_elems", ctypes.c_double), ("tiled_lead_elems", ctypes.c_double),
-                ("square_elems", ctypes.c_double)]
+                ("square_elems", ctypes.c_double),
+                ("n_sliced_blocks", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
 
 
 _lib = None
@@ -133,7 +134,19 @@ def _syrk(entry, A, C, alpha, beta, workspace, stream):
 
 
 def tbs_syrk_lower(A, C, alpha=1.0, beta=1.0, workspace=None, stream=None):
-    """C[lower] <- beta*C + alpha*A A^T under the Triangle Block Scheme, in place, asynchronous."""
+    """C[lower] <- beta*C + alpha*A A^T under the Triangle Block Scheme, in place, asynchronous.
+
+    workspace: a uint8 device tensor of at least tbs_syrk_lower_workspace() bytes; None allocates one of
+    that size for this call (on `stream`); False passes none (the library then uses its plan without
+    blocks cut along the contraction dimension)."""
+    if workspace is None:
+        import torch
+        need = tbs_syrk_lower_workspace(_dtype_code(A), A.shape[0], A.shape[1])
+        if need > 0:
+            with torch.cuda.stream(stream if stream is not None else torch.cuda.current_stream()):
+                workspace = torch.empty(need, dtype=torch.uint8, device=A.device)
+    elif workspace is False:
+        workspace = None
     return _syrk("tbs_syrk_lower", A, C, alpha, beta, workspace, stream)
 
 
@@ -144,21 +157,22 @@ def tbs_syrk_lower_square(A, C, alpha=1.0, beta=1.0, workspace=None, stream=None
 
 def tbs_syrk_lower_query(dtype_code, N, M, square=False) -> dict:
     info = PlanInfo()
-    st = load().tbs_syrk_lower_query(dtype_code, N, M, int(bool(square)), ctypes.byref(info))
+    st = load().tbs_syrk_lower_query(dtype_code, N, M, int(square), ctypes.byref(info))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_query")
     return {name: getattr(info, name) for name, _ in PlanInfo._fields_}
 
 
 def tbs_syrk_lower_enumerate(dtype_code, N, M, square=False) -> np.ndarray:
-    """The work list as an (n_items, 8) int32 array: kind, nrow, ncol, five tile-row slots."""
+    """The work list as an (n_items, 10) int32 array: kind, nrow, ncol, five tile-row slots, part, parts.
+    square: False/0 the plan used with a workspace, True/1 the square baseline, 2 the plan used without."""
     lib = load()
     n = ctypes.c_int64(0)
-    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(bool(square)), None, 0, ctypes.byref(n))
+    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(square), None, 0, ctypes.byref(n))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_enumerate")
-    out = np.empty((n.value, 8), dtype=np.int32)
-    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(bool(square)), out.ctypes.data, n.value,
+    out = np.empty((n.value, 10), dtype=np.int32)
+    st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(square), out.ctypes.data, n.value,
                                       ctypes.byref(n))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_enumerate")

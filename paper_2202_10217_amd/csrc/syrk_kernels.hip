@@ -316,6 +316,21 @@ __device__ __forceinline__ void store_strip(const Mats<T>& m, int row0, int col,
         }
 }
 
+// ---- blocks cut along the contraction dimension -------------------------------------------------
+// A sliced block is computed by `slices` workgroups, each over its share of the columns of A.  Every
+// one writes its accumulators to its own place in the workspace (in register order: coalesced, no
+// layout change), then adds one to the block's counter; the workgroup that finds the counter at
+// slices - 1 is the last: it reads all parts back, adds them in the order of the slices (so the
+// result does not depend on who finished when), and runs the ordinary epilogue on the sum.  No
+// workgroup ever waits for another.  part == nullptr: an ordinary, whole block.
+template <typename T>
+struct SliceCtx {
+    T* part = nullptr;              // this block's stretch of the workspace: [slices][NSLOT][16][256]
+    unsigned int* ctr = nullptr;    // parts finished so far (zero before and after the launch)
+    int* flag = nullptr;            // one int of LDS
+    int slices = 1, slice = 0;
+};
+
 // One block from start to end.  LDS holds two chunks; registers hold the operands of two k-steps
 // and one chunk in flight from global memory.  Per chunk: the operands of k-step s+1 are read from
 // LDS before the MFMAs of k-step s are issued; before the last k-step the next chunk is written to
@@ -327,9 +342,9 @@ __device__ __forceinline__ void store_strip(const Mats<T>& m, int row0, int col,
 //   test and no branch, so the accumulators stay in their registers across it.
 //   !FAST: anything else (ragged edges, odd leading dimensions, unusual slot sets); same schedule
 //   with every access checked.
-template <typename T, class Shape, uint32_t SLOTS, bool FAST>
+template <typename T, class Shape, uint32_t SLOTS, bool FAST, bool CAN_SLICE>
 __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
-                                           uint32_t dmask, T* lds)
+                                           uint32_t dmask, T* lds, const SliceCtx<T>& sc)
 {
     constexpr int NP = Shape::NP;
     constexpr int KC = Cfg<T>::KC, KS = KC / 4, LDK = Cfg<T>::LDK;
@@ -449,29 +464,83 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
       }
     }
 
+    if (CAN_SLICE && sc.part != nullptr) {                  // uniform
+        constexpr int NS = Shape::NSLOT;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            if (FAST ? ((SLOTS >> s) & 1u) != 0 : ((pmask >> s) & 1u) != 0) {
+                T* dst = sc.part + ((size_t)(sc.slice * NS + s) * 16) * kThreads + tid;
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) dst[(rb * 4 + g) * kThreads] = acc[s][rb][g];
+            }
+        __threadfence();                                    // the part is visible device-wide ...
+        __syncthreads();
+        if (tid == 0) *sc.flag = (atomicAdd(sc.ctr, 1u) == (unsigned)(sc.slices - 1)) ? 1 : 0;   // ... before the count
+        __syncthreads();
+        if (*sc.flag == 0) return;                          // not the last part of this block
+        __threadfence();
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            if (FAST ? ((SLOTS >> s) & 1u) != 0 : ((pmask >> s) & 1u) != 0) {
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) acc[s][rb][g] = T(0);
+                // two parts are requested together (32 loads in flight per lane), then added in order
+                for (int sl0 = 0; sl0 < sc.slices; sl0 += 2) {
+                    T v[2][16];
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        const int sl = min(sl0 + d, sc.slices - 1);
+                        const T* src = sc.part + ((size_t)(sl * NS + s) * 16) * kThreads + tid;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) v[d][e] = src[e * kThreads];
+                    }
+#pragma unroll
+                    for (int d = 0; d < 2; ++d)
+                        if (sl0 + d < sc.slices) {          // uniform
+#pragma unroll
+                            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                                for (int g = 0; g < 4; ++g) acc[s][rb][g] += v[d][rb * 4 + g];
+                        }
+                }
+            }
+        if (tid == 0) *sc.ctr = 0u;                         // for the next launch that uses this counter
+    }
+
     // Epilogue.
     const int col16 = w * 16 + (lane & 15);
     if constexpr (FAST) {
-        // all old values of the block are requested at once (the operand registers of the loop are
-        // free now), then every strip is computed and stored
-        TileStrip<T> old[Shape::NSLOT];
+        // the old values of three tiles are requested at once (the operand registers of the loop are
+        // free now), then their strips are computed and stored
         const bool rd = m.beta != T(0);
 #pragma unroll
-        for (int i = 0; i < Shape::NA; ++i)
+        for (int s0 = 0; s0 < Shape::NSLOT; s0 += 3) {      // three tiles' old values in flight at a time
+            TileStrip<T> old[3];
 #pragma unroll
-            for (int j = 0; j < Shape::NB; ++j)
-                if (slot_on<Shape>(SLOTS, i, j) && rd)
-                    old[Shape::slot(i, j)].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
-                                                                prow[Shape::b_panel(j)] * kTile + col16, lane,
-                                                                ((dmask >> Shape::slot(i, j)) & 1u) != 0);
+            for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
-        for (int i = 0; i < Shape::NA; ++i)
+                for (int j = 0; j < Shape::NB; ++j) {
+                    const int sl = Shape::slot(i, j);
+                    if (slot_on<Shape>(SLOTS, i, j) && sl >= s0 && sl < s0 + 3 && rd)
+                        old[sl - s0].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
+                                                          prow[Shape::b_panel(j)] * kTile + col16, lane,
+                                                          ((dmask >> sl) & 1u) != 0);
+                }
 #pragma unroll
-            for (int j = 0; j < Shape::NB; ++j)
-                if (slot_on<Shape>(SLOTS, i, j))
-                    store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
-                                          prow[Shape::b_panel(j)] * kTile + col16, lane, acc[Shape::slot(i, j)],
-                                          old[Shape::slot(i, j)], ((dmask >> Shape::slot(i, j)) & 1u) != 0);
+            for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+                for (int j = 0; j < Shape::NB; ++j) {
+                    const int sl = Shape::slot(i, j);
+                    if (slot_on<Shape>(SLOTS, i, j) && sl >= s0 && sl < s0 + 3)
+                        store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
+                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[sl], old[sl - s0],
+                                              ((dmask >> sl) & 1u) != 0);
+                }
+        }
 #ifdef TBS_TRACE
         if (tid == 0) atomicAdd(&g_phase[1], wall_clock64() - phase_mark);
 #endif
@@ -509,9 +578,9 @@ template <> struct FastSets<RectShape> {
     }
 };
 
-template <typename T, class Shape, int IDX>
+template <typename T, class Shape, int IDX, bool CAN_SLICE>
 __device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
-                                         uint32_t dmask, T* lds)
+                                         uint32_t dmask, T* lds, const SliceCtx<T>& sc)
 {
     if constexpr (IDX < FastSets<Shape>::N) {
         constexpr uint32_t SLOTS = FastSets<Shape>::set(IDX);
@@ -525,18 +594,19 @@ __device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Sha
                     whole = whole && (prow[p] + 1) * kTile <= nrows;
                 }
             if (!whole) return false;
-            block_body<T, Shape, SLOTS, true>(m, prow, pmask, dmask, lds);
+            block_body<T, Shape, SLOTS, true, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
             return true;
         }
-        return try_fast<T, Shape, IDX + 1>(m, prow, pmask, dmask, lds);
+        return try_fast<T, Shape, IDX + 1, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
     } else {
         return false;
     }
 }
 
 // with_diag: tiles (r, r) belong to the block (their part on and below the diagonal)
-template <typename T, class Shape>
-__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds, bool with_diag = false)
+template <typename T, class Shape, bool CAN_SLICE = true>
+__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds, const SliceCtx<T>& sc,
+                                          bool with_diag = false)
 {
     constexpr int NP = Shape::NP;
     int prow[NP];
@@ -561,27 +631,53 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
     const bool fast_ok = m.M >= KC && m.M % KC == 0 && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
                          (int64_t)m.nr * m.ldr * (int64_t)sizeof(T) < lim &&
                          (int64_t)m.nq * m.ldq * (int64_t)sizeof(T) < lim;
-    if (fast_ok && try_fast<T, Shape, 0>(m, prow, pmask, dmask, lds)) return;
-    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false>(m, prow, pmask, dmask, lds);
+    if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
+    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
 }
 
 // ---- the kernels: workgroup -> block(s) -> code path ------------------------------------------
+// Where the sliced blocks of a launch keep their parts and counters.
 template <typename T>
-__device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mats<T>& m, T* lds)
+struct SliceSpace {
+    T* ws = nullptr;                // workspace: n_ws_blocks stretches of ws_slices * 6 * 16 * 256 elements
+    unsigned int* ctr = nullptr;    // one counter per sliced block
+    int* flag = nullptr;            // one int of LDS
+};
+
+template <typename T>
+__device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mats<T>& m0, T* lds,
+                                         const SliceSpace<T>& sp)
 {
     Item it;
     tbs_decode(plan, id, it);
+    Mats<T> m = m0;
+    SliceCtx<T> sc;
+    if (it.slices > 1 && it.kind != kEmpty) {
+        // part `slice` of the columns of A, in whole chunks (the last part takes the ragged end)
+        constexpr int KC = Cfg<T>::KC;
+        const int64_t nch = (m0.M + KC - 1) / KC;
+        const int64_t k0 = nch * it.slice / it.slices * KC;
+        const int64_t k1 = (it.slice + 1 == it.slices) ? (int64_t)m0.M : nch * (it.slice + 1) / it.slices * KC;
+        m.R = m0.R + k0;
+        m.Q = m0.Q + k0;
+        m.M = (int)(k1 > k0 ? k1 - k0 : 0);
+        sc.part = sp.ws + (size_t)it.ws_block * ((size_t)plan.ws_slices * 6 * 16 * kThreads);
+        sc.ctr = sp.ctr + it.ws_block;
+        sc.flag = sp.flag;
+        sc.slices = it.slices;
+        sc.slice = it.slice;
+    }
     if (it.kind == kTri) {
-        run_block<T, TriShape>(it, m, lds);
+        run_block<T, TriShape>(it, m, lds, sc);
     } else if (it.kind == kRect) {
-        run_block<T, RectShape>(it, m, lds);
+        run_block<T, RectShape>(it, m, lds, sc);
     } else if (it.kind == kRectDiag) {
-        run_block<T, RectShape>(it, m, lds, true);
+        run_block<T, RectShape>(it, m, lds, sc, true);
     } else if (it.kind == kDiag) {                          // a 1 x 1 rectangle on the diagonal
         Item d = it;
         d.rows[0] = it.rows[0];
         d.rows[kRectCols] = it.rows[0];
-        run_block<T, RectShape>(d, m, lds, true);
+        run_block<T, RectShape>(d, m, lds, sc, true);
     }
 }
 
@@ -590,11 +686,14 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
 template <typename T>
 __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, int M, T alpha,
                                                             const T* __restrict__ A, int64_t lda,
-                                                            T beta, T* __restrict__ C, int64_t ldc)
+                                                            T beta, T* __restrict__ C, int64_t ldc, T* ws,
+                                                            unsigned int* slice_ctr)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
+    __shared__ int s_flag;
     const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
-    run_item<T>(plan, (int32_t)blockIdx.x, m, reinterpret_cast<T*>(smem));
+    const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
+    run_item<T>(plan, (int32_t)blockIdx.x, m, reinterpret_cast<T*>(smem), sp);
 }
 
 // Persistent form: a fixed number of workgroups (at most one per compute unit; fewer when the caller
@@ -621,11 +720,14 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, int N, int M, T alpha,
                                                                        const T* __restrict__ A, int64_t lda,
                                                                        T beta, T* __restrict__ C, int64_t ldc,
-                                                                       unsigned int* ctr)
+                                                                       unsigned int* ctr, T* ws,
+                                                                       unsigned int* slice_ctr)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
     __shared__ int32_t s_item;
+    __shared__ int s_flag;
     const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
+    const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
     for (;;) {
         __syncthreads();                        // the previous block's LDS reads and s_item are done with
         if (threadIdx.x == 0) s_item = (int32_t)atomicAdd(&ctr[0], 1u);
@@ -635,7 +737,7 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
 #ifdef TBS_TRACE
         const unsigned long long t_start = wall_clock64();
 #endif
-        run_item<T>(plan, id, m, reinterpret_cast<T*>(smem));
+        run_item<T>(plan, id, m, reinterpret_cast<T*>(smem), sp);
 #ifdef TBS_TRACE
         if (threadIdx.x == 0 && id < kTraceItems) {
             g_trace[id][0] = t_start;
@@ -658,6 +760,10 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
 // Launches that may run at the same time must use different pairs: they are handed out round robin.
 constexpr int kCounterPairs = 64;
 __device__ unsigned int g_syrk_counters[kCounterPairs][2];
+// Counters of the sliced blocks of a launch (parts finished), one set per launch in flight, handed
+// out like the pairs above; zero at load time, set back to zero by the workgroup that sums a block.
+constexpr int kSliceCounters = 512;
+__device__ unsigned int g_slice_counters[kCounterPairs][kSliceCounters];
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, rectangular blocks of mr x nc tiles
 // (mr <= 2, nc <= 3), one workgroup per block.
@@ -686,48 +792,69 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
         it.rows[kRectCols + r] = (r < mr && t < Tm) ? t : -1;
     }
     const Mats<T> m = {R, ldr, m_rows, Q, ldq, n_cols, C, ldc, K, alpha, beta, false};
-    run_block<T, RectShape>(it, m, lds);
+    run_block<T, RectShape, false>(it, m, lds, SliceCtx<T>{});
 }
 
 template <typename T>
 static hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                                int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups,
+                                int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* ws,
                                 hipStream_t stream)
 {
     if (plan.n_items <= 0) return hipSuccess;
-    if (max_workgroups <= 0 || plan.n_items <= max_workgroups) {
+    if (plan.n_ws_blocks > kSliceCounters || (plan.n_ws_blocks > 0 && ws == nullptr)) return hipErrorInvalidValue;
+    const bool persistent = max_workgroups > 0 && plan.n_items > max_workgroups;
+    unsigned int* ctr = nullptr;
+    unsigned int* slice_ctr = nullptr;
+    if (persistent || plan.n_ws_blocks > 0) {
+        // addresses of the counter arrays on the current device, looked up once per device
+        static std::mutex mu;
+        static unsigned int* base[64] = {nullptr};
+        static unsigned int* sbase[64] = {nullptr};
+        static std::atomic<unsigned> next_pair{0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        {
+            std::lock_guard<std::mutex> lock(mu);
+            if (!base[dev]) {
+                void* ptr = nullptr;
+                e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_syrk_counters));
+                if (e != hipSuccess) return e;
+                void* sptr = nullptr;
+                e = hipGetSymbolAddress(&sptr, HIP_SYMBOL(g_slice_counters));
+                if (e != hipSuccess) return e;
+                base[dev] = static_cast<unsigned int*>(ptr);
+                sbase[dev] = static_cast<unsigned int*>(sptr);
+            }
+        }
+        const unsigned pair = next_pair.fetch_add(1) % kCounterPairs;
+        ctr = base[dev] + 2 * pair;
+        slice_ctr = sbase[dev] + (size_t)kSliceCounters * pair;
+    }
+    if (!persistent) {
         hipLaunchKernelGGL(tbs_syrk_kernel<T>, dim3((unsigned)plan.n_items), dim3(kThreads), 0, stream, plan,
-                           (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc);
+                           (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc, (T*)ws, slice_ctr);
         return hipGetLastError();
     }
-    // address of the counter array on the current device, looked up once per device
-    static std::mutex mu;
-    static unsigned int* base[64] = {nullptr};
-    static std::atomic<unsigned> next_pair{0};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    {
-        std::lock_guard<std::mutex> lock(mu);
-        if (!base[dev]) {
-            void* ptr = nullptr;
-            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_syrk_counters));
-            if (e != hipSuccess) return e;
-            base[dev] = static_cast<unsigned int*>(ptr);
-        }
-    }
-    unsigned int* ctr = base[dev] + 2 * (next_pair.fetch_add(1) % kCounterPairs);
     hipLaunchKernelGGL(tbs_syrk_persistent_kernel<T>, dim3((unsigned)max_workgroups), dim3(kThreads), 0, stream,
-                       plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc, ctr);
+                       plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc, ctr, (T*)ws,
+                       slice_ctr);
     return hipGetLastError();
 }
 
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, hipStream_t stream)
+                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
+                       hipStream_t stream)
 {
-    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, stream)
-               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, stream);
+    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, stream)
+               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace,
+                                       stream);
+}
+
+size_t syrk_workspace_bytes(bool f32, const Plan& plan)
+{
+    return (size_t)plan.n_ws_blocks * (size_t)plan.ws_slices * 6 * 16 * kThreads * (f32 ? 4 : 8);
 }
 
 // The block shape is the one with the shortest estimated time on `units` compute units: rounds of

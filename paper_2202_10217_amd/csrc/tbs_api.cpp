@@ -44,32 +44,46 @@ int32_t compute_units()
 // compared with the fixed cost of a block (prologue, epilogue, dispatch: about 20 us against
 // M * 2 * 64 * 64 flops at one compute unit's share of the MFMA peak), which decides how finely the
 // tail of the work list is cut.  M enters through its power-of-two bucket.  Built once, kept.
-const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M)
+const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M, bool sliced)
 {
     static std::mutex mu;
-    static std::map<std::tuple<int32_t, bool, int32_t, int32_t>, tbs::Plan> cache;
+    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool>, tbs::Plan> cache;
     int32_t bucket = 0;
     while (bucket < 30 && ((int64_t)3 << bucket) / 2 <= M) ++bucket;     // M ~ 2^bucket
     std::lock_guard<std::mutex> lock(mu);
-    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket);
+    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket, sliced);
     auto it = cache.find(key);
     if (it == cache.end()) {
         const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
         const double overhead_tiles = 20.0 / tile_us;
         tbs::Plan p;
-        // TBS_PLAN_TUNING="levels,rows,cols,base,zone_rows,zone_cols" pins the tuning the planner would
-        // otherwise choose (for measurements; every tuning covers each tile exactly once)
-        const char* pin = square ? nullptr : std::getenv("TBS_PLAN_TUNING");
         // TBS_PLAN_FAMILY=cyclic: the paper's cyclic family only (no power-of-two moduli)
         const char* famenv = std::getenv("TBS_PLAN_FAMILY");
         const bool xor_family = !(famenv && famenv[0] == 'c');
-        int lv = 0, mr = 0, nc = 0, base = 0, mrd = 0, ncd = 0;
-        if (pin && std::sscanf(pin, "%d,%d,%d,%d,%d,%d", &lv, &mr, &nc, &base, &mrd, &ncd) >= 4 && lv >= 0 &&
-            lv <= tbs::kMaxLevels && mr >= 1 && mr <= tbs::kRectRows && nc >= 1 && nc <= tbs::kRectCols) {
+        // blocks may be cut along the contraction dimension while a part keeps at least 8 chunks of
+        // the smallest M of the bucket; TBS_SYRK_SLICES=0 turns that off, "levels,rows,...,tri,rect,
+        // tail_blocks,tail" in TBS_PLAN_TUNING pins it
+        const char* slenv = std::getenv("TBS_SYRK_SLICES");
+        const int64_t kc = dtype == TBS_F32 ? 32 : 16;
+        const int64_t m_low = ((int64_t)3 << bucket) / 4;
+        int32_t max_slices = (int32_t)std::min<int64_t>(tbs::kMaxSlices, m_low / (8 * kc));
+        if (!sliced || square || (slenv && slenv[0] == '0')) max_slices = 1;
+        // TBS_PLAN_TUNING="levels,rows,cols,base,zone_rows,zone_cols[,tri,rect,tail_blocks,tail]" pins
+        // the tuning the planner would otherwise choose (for measurements; every tuning covers each
+        // tile exactly once)
+        const char* pin = square ? nullptr : std::getenv("TBS_PLAN_TUNING");
+        int lv = 0, mr = 0, nc = 0, base = 0, mrd = 0, ncd = 0, st = 1, sr = 1, tb = 0, ts = 1;
+        if (pin && std::sscanf(pin, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &lv, &mr, &nc, &base, &mrd, &ncd, &st, &sr, &tb,
+                               &ts) >= 4 &&
+            lv >= 0 && lv <= tbs::kMaxLevels && mr >= 1 && mr <= tbs::kRectRows && nc >= 1 && nc <= tbs::kRectCols) {
             tbs::PlanTuning tune{lv, mr, nc, base != 0, mrd, ncd};
             tune.xor_family = xor_family;
             if (!tbs::build_plan(T, tune, &p)) return nullptr;
-        } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family)) {
+            if (max_slices > 1 && (st > 1 || sr > 1 || (tb > 0 && ts > 1))) {
+                tbs::Plan q;
+                if (tbs::apply_slicing(p, tbs::Slicing{st, sr, tb, ts}, &q)) p = q;
+            }
+        } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family, max_slices)) {
             return nullptr;
         }
         it = cache.emplace(key, p).first;
@@ -88,12 +102,28 @@ tbs_status check_syrk(tbs_dtype dtype, int64_t N, int64_t M, const void* A, int6
     return TBS_OK;
 }
 
+// The plan a call uses: the one with sliced blocks if the caller's workspace holds its parts, else the
+// one without.
+const tbs::Plan* plan_for_call(int32_t T, bool square, tbs_dtype dtype, int64_t M, const void* workspace,
+                               size_t workspace_bytes)
+{
+    const size_t es = dtype == TBS_F32 ? 4 : 8;
+    const tbs::Plan* sliced = cached_plan(T, square, dtype, M, true);
+    if (!sliced) return nullptr;
+    if (sliced->n_ws_blocks == 0) return sliced;
+    const size_t need = tbs::syrk_workspace_bytes(dtype == TBS_F32, *sliced);
+    if (workspace != nullptr && workspace_bytes >= need && (reinterpret_cast<uintptr_t>(workspace) % es) == 0)
+        return sliced;
+    return cached_plan(T, square, dtype, M, false);
+}
+
 tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,
-                     int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream, int reserve_units = 0)
+                     int64_t lda, double beta, void* C, int64_t ldc, hipStream_t stream, int reserve_units = 0,
+                     void* workspace = nullptr, size_t workspace_bytes = 0)
 {
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, square, dtype, M);
+    const tbs::Plan* plan = plan_for_call(T, square, dtype, M, workspace, workspace_bytes);
     if (!plan) return TBS_EINVAL;
     static const bool persistent = [] {
         const char* v = std::getenv("TBS_SYRK_PERSISTENT");
@@ -106,8 +136,8 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
         return (n > 0 && n < 4096) ? (int)n : 0;
     }();
     const int wgs = persistent ? std::max(1, compute_units() - std::max(reserve_units, env_reserve)) : 0;
-    const hipError_t e =
-        tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, wgs, stream);
+    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, wgs,
+                                          workspace, stream);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 
@@ -306,6 +336,11 @@ tbs_status tbs_syrk_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_
 {
     if (!dtype_ok(dtype) || N < 0 || M < 0 || N > kMaxN || M > kMaxM || !bytes) return TBS_EINVAL;
     *bytes = 0;
+    if (N == 0) return TBS_OK;
+    const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    const tbs::Plan* plan = cached_plan(T, false, dtype, M, true);
+    if (!plan) return TBS_EINVAL;
+    *bytes = tbs::syrk_workspace_bytes(dtype == TBS_F32, *plan);
     return TBS_OK;
 }
 
@@ -313,11 +348,10 @@ tbs_status tbs_syrk_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha, c
                           double beta, void* C, int64_t ldc, void* workspace, size_t workspace_bytes,
                           void* hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     const tbs_status st = check_syrk(dtype, N, M, A, lda, C, ldc);
     if (st != TBS_OK) return st;
-    return syrk_impl(false, dtype, N, M, alpha, A, lda, beta, C, ldc, (hipStream_t)hip_stream);
+    return syrk_impl(false, dtype, N, M, alpha, A, lda, beta, C, ldc, (hipStream_t)hip_stream, 0, workspace,
+                     workspace_bytes);
 }
 
 tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,
@@ -335,7 +369,7 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
 {
     if (!dtype_ok(dtype) || N < 0 || M < 0 || N > kMaxN || M > kMaxM || !out) return TBS_EINVAL;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, square != 0, dtype, M);
+    const tbs::Plan* plan = cached_plan(T, square == 1, dtype, M, square == 0);
     if (!plan) return TBS_EINVAL;
     tbs::PlanStats st;
     tbs::plan_stats(*plan, N, M, &st);
@@ -346,6 +380,9 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
     r.c = st.levels > 0 ? plan->c[0] : 0;
     r.l = st.levels > 0 ? T - kK * plan->c[0] : T;
     r.family = st.levels > 0 ? plan->fam[0] : 0;
+    r.max_slices = plan->n_ws_blocks > 0 ? plan->ws_slices : 1;
+    r.n_sliced_blocks = plan->n_ws_blocks;
+    r.workspace_bytes = (int64_t)tbs::syrk_workspace_bytes(dtype == TBS_F32, *plan);
     r.tile_rows = T;
     r.n_items = plan->n_items;
     r.n_tri_blocks = st.n_tri;
@@ -370,7 +407,7 @@ tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32
 {
     if (!dtype_ok(dtype) || N < 0 || N > kMaxN || M < 0 || M > kMaxM || !n_items) return TBS_EINVAL;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, square != 0, dtype, M);
+    const tbs::Plan* plan = cached_plan(T, square == 1, dtype, M, square == 0);
     if (!plan) return TBS_EINVAL;
     *n_items = plan->n_items;
     if (!items) return TBS_OK;
@@ -378,11 +415,13 @@ tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32
     for (int32_t t = 0; t < plan->n_items; ++t) {
         tbs::Item it;
         tbs::tbs_decode(*plan, t, it);
-        int32_t* o = items + (int64_t)t * 8;
+        int32_t* o = items + (int64_t)t * 10;
         o[0] = it.kind;
         o[1] = it.nrow;
         o[2] = it.ncol;
         for (int s = 0; s < 5; ++s) o[3 + s] = it.rows[s];
+        o[8] = it.slice;
+        o[9] = it.slices;
     }
     return TBS_OK;
 }

@@ -59,6 +59,12 @@ struct Seg {
     int32_t nI, nJ;    // kSegRect: blocks per zone along rows / columns
     int32_t mr, nc;    // kSegRect: block shape in tiles
     int32_t diag;      // kSegRect: 1 = the columns reach the diagonal and tiles (r, r) belong to the blocks
+    // Slicing along the contraction dimension: every block of the segment is `slices` consecutive
+    // items, item s of a block takes the s-th part of the columns of A; the parts are summed in order
+    // by the last one to finish (see the kernels).  `t0`: the segment covers the blocks t0, t0 + 1, ...
+    // of the enumeration described above (a list of blocks may be cut into two segments that are
+    // sliced differently).  `ws0`: number of this segment's first block among all sliced blocks.
+    int32_t slices, t0, ws0;
 };
 
 struct Plan {
@@ -68,6 +74,8 @@ struct Plan {
     int32_t n_items;
     int32_t c[kMaxLevels];      // modulus of each level that has triangle blocks
     int32_t fam[kMaxLevels];    // 0: cyclic family; m > 0: the XOR family with c = 2^m
+    int32_t n_ws_blocks;        // sliced blocks (each owns a stretch of the workspace)
+    int32_t ws_slices;          // largest `slices` of any segment (the workspace stride per block)
     Seg seg[kMaxSegs];
 };
 
@@ -78,6 +86,8 @@ struct Item {
     // tile rows, -1 = unused.  Triangle block: R in zone order in slots 0..k-1.  Rectangle: column
     // side in slots 0..2, row side in slots 3..4.  Diagonal tile: slot 0.
     int32_t rows[kMaxPanels];
+    int32_t slice, slices;      // this item is part `slice` of `slices` of its block (0 of 1: the whole block)
+    int32_t ws_block;           // sliced blocks: which stretch of the workspace
 };
 
 // first tile row of zone z of a level: the zone is reached by choosing digit d_m at level m
@@ -96,12 +106,21 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
     it.kind = kEmpty;
     it.nrow = 0;
     it.ncol = 0;
+    it.slice = 0;
+    it.slices = 1;
+    it.ws_block = -1;
     for (int s = 0; s < kMaxPanels; ++s) it.rows[s] = -1;
     int32_t si = 0;
     while (si + 1 < p.nseg && id >= p.seg[si + 1].first) ++si;
     const Seg& sg = p.seg[si];
-    const int32_t t = id - sg.first;
-    if (t < 0 || t >= sg.count) return;
+    const int32_t item = id - sg.first;
+    if (item < 0 || item >= sg.count) return;
+    const int32_t S = sg.slices > 1 ? sg.slices : 1;
+    const int32_t blk = item / S;
+    it.slice = item - blk * S;
+    it.slices = S;
+    if (S > 1) it.ws_block = sg.ws0 + blk;
+    const int32_t t = sg.t0 + blk;
     if (sg.kind == kSegTri) {
         const int32_t c = p.c[sg.level];
         const int32_t z = t / (c * c);

@@ -112,6 +112,9 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
     int32_t n = 0, first = 0;
     auto push = [&](Seg s) {
         if (s.count <= 0) return;
+        s.slices = 1;
+        s.t0 = 0;
+        s.ws0 = 0;
         s.first = first;
         first += s.count;
         p.seg[n++] = s;
@@ -135,6 +138,59 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
     }
     p.nseg = n;
     p.n_items = first;
+    p.n_ws_blocks = 0;
+    p.ws_slices = 1;
+    *out = p;
+    return true;
+}
+
+bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
+{
+    Plan p = base;
+    std::vector<Seg> segs;
+    for (int32_t i = 0; i < base.nseg; ++i) {
+        Seg s = base.seg[i];                                // unsliced: count = blocks, t0 = 0
+        s.slices = (s.kind == kSegTri || s.kind == kSegTriBase) ? sl.tri : sl.rect;
+        segs.push_back(s);
+    }
+    if (sl.tail_blocks > 0 && sl.tail > 1 && !segs.empty()) {   // the end of the list, cut more finely
+        int32_t want = sl.tail_blocks;
+        std::vector<Seg> tail;
+        while (want > 0 && !segs.empty()) {
+            Seg& last = segs.back();
+            const int32_t take = std::min(want, last.count);
+            Seg cut = last;
+            cut.t0 = last.t0 + last.count - take;
+            cut.count = take;
+            cut.slices = std::max(sl.tail, last.slices);
+            tail.insert(tail.begin(), cut);
+            last.count -= take;
+            want -= take;
+            if (last.count == 0) segs.pop_back();
+        }
+        segs.insert(segs.end(), tail.begin(), tail.end());
+    }
+    if ((int32_t)segs.size() > kMaxSegs) return false;
+    int32_t first = 0, ws = 0, smax = 1;
+    p.nseg = 0;
+    for (Seg s : segs) {
+        if (s.slices < 1) s.slices = 1;
+        if (s.slices > kMaxSlices) return false;
+        s.first = first;
+        s.ws0 = 0;
+        if (s.slices > 1) {
+            s.ws0 = ws;
+            ws += s.count;
+            smax = std::max(smax, s.slices);
+        }
+        s.count *= s.slices;                                // items
+        first += s.count;
+        p.seg[p.nseg++] = s;
+    }
+    if (ws > kMaxSliceBlocks) return false;
+    p.n_items = first;
+    p.n_ws_blocks = ws;
+    p.ws_slices = smax;
     *out = p;
     return true;
 }
@@ -162,6 +218,7 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
         } else {
             continue;                                       // empty block: exits at once
         }
+        if (it.slices > 1) tiles = tiles / it.slices + 0.03;   // plus its share of summing the parts
         const double start = free_at.top();
         free_at.pop();
         const double stop = start + tiles + overhead_tiles;
@@ -171,7 +228,8 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
     return end;
 }
 
-bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family)
+bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family,
+                 int32_t max_slices)
 {
     if (square) return build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out);
     PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
@@ -181,6 +239,33 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
     if (per_unit > 200.0 || T < 2) return true;
     double best = simulate_makespan(*out, ncu, overhead_tiles);
+    // cutting blocks along the contraction dimension costs a workspace and an extra pass over the
+    // parts: only for problems with few tiles per compute unit, and only for a clear gain
+    const bool slicing = max_slices > 1 && per_unit <= 40.0;
+    double best_sliced = best;
+    Plan sliced = *out;
+    bool have_sliced = false;
+    auto try_slicings = [&](const Plan& base) {
+        const int32_t whole[3] = {1, 2, 4};
+        const int32_t tails[5][2] = {{0, 1}, {16, 16}, {32, 8}, {64, 4}, {128, 4}};
+        for (int32_t st : whole)
+            for (int32_t sr : whole)
+                for (const auto& tl : tails) {
+                    if (st == 1 && sr == 1 && tl[0] == 0) continue;
+                    if (st > max_slices || sr > max_slices || tl[1] > max_slices) continue;
+                    Plan q;
+                    if (!apply_slicing(base, Slicing{st, sr, tl[0], tl[1]}, &q)) continue;
+                    // at most 128 MB of workspace (6 tiles of doubles per part)
+                    if ((int64_t)q.n_ws_blocks * q.ws_slices * 6 * kTile * kTile * 8 > ((int64_t)128 << 20)) continue;
+                    const double span = simulate_makespan(q, ncu, overhead_tiles);
+                    if (span < best_sliced * 0.995) {
+                        best_sliced = span;
+                        sliced = q;
+                        have_sliced = true;
+                    }
+                }
+    };
+    if (slicing) try_slicings(*out);
     const int32_t shapes[5][2] = {{2, 3}, {2, 2}, {1, 3}, {1, 2}, {1, 1}};
     for (int32_t levels = kMaxLevels; levels >= 0; levels = (levels == kMaxLevels) ? 2 : levels - 1) {
         for (const auto& sh : shapes) {
@@ -194,9 +279,11 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
                     best = span;
                     *out = cand;
                 }
+                if (slicing && sh[0] == 1) try_slicings(cand);
             }
         }
     }
+    if (have_sliced && best_sliced < best * 0.97) *out = sliced;
     return true;
 }
 
@@ -214,24 +301,26 @@ void plan_stats(const Plan& p, int64_t N, int64_t M, PlanStats* st)
         for (int32_t t = 0; t < sg.count; ++t) {
             Item it;
             tbs_decode(p, sg.first + t, it);
+            const bool head = it.slice == 0;                // blocks are counted once, at their first part
             double a = 0;
             if (it.kind == kTri) {
-                ++r.n_tri;
+                if (head) ++r.n_tri;
                 for (int32_t u = 0; u < it.nrow; ++u) a += panel_rows(it.rows[u]);
             } else if (it.kind == kRect || it.kind == kRectDiag) {
-                ++r.n_rect;
+                if (head) ++r.n_rect;
                 for (int32_t u = 0; u < kMaxPanels; ++u)
                     if (it.rows[u] >= 0) a += panel_rows(it.rows[u]);
-                if (it.kind == kRectDiag)
+                if (it.kind == kRectDiag && head)
                     for (int32_t q = 0; q < kRectCols; ++q)
                         for (int32_t rr = 0; rr < kRectRows; ++rr)
                             if (it.rows[q] >= 0 && it.rows[q] == it.rows[kRectCols + rr]) ++r.n_diag;
             } else if (it.kind == kDiag) {
-                ++r.n_diag;
+                if (head) ++r.n_diag;
                 a += panel_rows(it.rows[0]);
             } else {
                 ++r.n_empty;
             }
+            a /= (double)it.slices;                         // a part loads its share of the columns
             r.A_elems += a * (double)M;
             if (sg.kind == kSegTri && sg.level == 0) r.A_elems_top += a * (double)M;
         }

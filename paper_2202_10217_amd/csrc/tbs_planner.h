@@ -20,6 +20,19 @@ struct PlanTuning {
     bool xor_family = true;  // levels may use c = 2^m with the XOR family where that covers more rows
 };
 
+// How the blocks of a plan are cut along the contraction dimension (1 = not at all): all triangle
+// blocks, all rectangular blocks, and the last `tail_blocks` blocks of the list (the ones that decide
+// when the last compute unit finishes) more finely.
+struct Slicing {
+    int32_t tri = 1, rect = 1, tail_blocks = 0, tail = 1;
+};
+constexpr int32_t kMaxSliceBlocks = 512;   // sliced blocks per plan (each has a counter and workspace)
+constexpr int32_t kMaxSlices = 32;
+
+// Rewrites the segments of an unsliced plan for the given slicing; false if it does not fit the
+// descriptor (too many segments or sliced blocks).
+bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out);
+
 // Plan for a matrix of T tile rows with the given tuning.  Returns false when T is out of range for
 // the descriptor.
 bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
@@ -29,7 +42,9 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
 // few blocks, the candidates differ in how finely the diagonal zones and the last tile rows are cut,
 // and the one with the shortest simulated makespan on `ncu` compute units is taken (blocks are
 // dispatched in list order to the first free unit; a block costs its tiles plus `overhead_tiles`).
-bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family = true);
+// max_slices > 1 lets the choice cut blocks along the contraction dimension (at most that finely).
+bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family = true,
+                 int32_t max_slices = 1);
 
 // Makespan, in tile units, of dispatching the plan's blocks in order onto ncu units.
 double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles);

@@ -63,7 +63,12 @@ def test_syrk_argument_checks(lib, entry):
 
 
 def test_workspace_queries(lib):
-    assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, 4096, 4096) == 0
+    big = tb.tbs_syrk_lower_query(tb.TBS_F64, 32768, 512)
+    assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, 32768, 512) == 0 == big["workspace_bytes"]   # many blocks per unit
+    small = tb.tbs_syrk_lower_query(tb.TBS_F64, 2048, 4096)
+    assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, 2048, 4096) == small["workspace_bytes"]
+    assert small["workspace_bytes"] == small["n_sliced_blocks"] * small["max_slices"] * 6 * 4096 * 8
+    assert tb.tbs_syrk_lower_query(tb.TBS_F64, 2048, 4096, 2)["workspace_bytes"] == 0        # plan without workspace
     n64 = tb.tbs_potrf_lower_workspace(tb.TBS_F64, 1000)
     n32 = tb.tbs_potrf_lower_workspace(tb.TBS_F32, 1000)
     assert n64 >= 4 and n32 >= 4                              # at least the info word

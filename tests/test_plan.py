@@ -24,8 +24,19 @@ def _lib():
 
 
 def _tiles_of(items):
-    """Yields (row tile, column tile) for every tile the work list updates."""
-    for kind, nrow, ncol, *rows in items.tolist():
+    """Yields (row tile, column tile) for every tile the work list updates.  A block that is cut along
+    the contraction dimension appears as consecutive items, part 0 .. parts-1 of the same block: its
+    tiles are yielded once, and the run of parts is checked."""
+    rows_list = items.tolist()
+    for idx, (kind, nrow, ncol, *rest) in enumerate(rows_list):
+        rows, part, parts = rest[:5], rest[5], rest[6]
+        assert 0 <= part < parts
+        if parts > 1:                                       # the parts of a block follow each other
+            head = rows_list[idx - part]
+            assert head[:8] == [kind, nrow, ncol] + rows and head[8] == 0 and head[9] == parts
+            assert idx - part + parts <= len(rows_list)
+        if part != 0:
+            continue
         if kind == KIND_TRI:
             R = rows[:nrow]
             assert all(r >= 0 for r in R) and all(r < 0 for r in rows[nrow:])
@@ -108,7 +119,7 @@ def test_triangle_blocks_are_those_of_the_indexing_family(N, M):
     want = {lv: sorted(tuple(off + r for r in R) for l2, off, R in io.blocks if l2 == lv)
             for lv in range(10)}
     all_want = set(sum(want.values(), []))
-    lib_tri = [tuple(row[3:3 + K]) for row in items.tolist() if row[0] == KIND_TRI and row[1] == K]
+    lib_tri = [tuple(row[3:3 + K]) for row in items.tolist() if row[0] == KIND_TRI and row[1] == K and row[8] == 0]
     family = [R for R in lib_tri if _is_family_block(R)]
     info = tb.tbs_syrk_lower_query(tb.TBS_F64, T * B, M)
     fam, c = ts.choose_family(T // K, K)

@@ -281,3 +281,36 @@ def test_calls_on_several_streams_do_not_disturb_each_other(tb):
     for i in range(3):
         assert np.array_equal(dCs[i].cpu().numpy()[il], refs[i][il]), i
     assert np.array_equal(np.tril(dS.cpu().numpy()), G)
+
+
+@pytest.mark.parametrize("N,M", [(512, 4096), (2048, 2080), (1100, 3000)])
+def test_blocks_cut_along_the_contraction_dimension(tb, N, M):
+    # few tiles per compute unit and a long contraction: with a workspace the library computes blocks in
+    # parts (summed in a fixed order by the last part to finish), without one it does not.  Same bits on
+    # integer data either way, repeatably; the plan with a workspace really is cut; the tolerance holds
+    # on random data with ragged sizes too.
+    info = tb.tbs_syrk_lower_query(tb.TBS_F64, N, M)
+    assert info["n_sliced_blocks"] > 0 and info["workspace_bytes"] == tb.tbs_syrk_lower_workspace(tb.TBS_F64, N, M)
+    assert tb.tbs_syrk_lower_query(tb.TBS_F64, N, M, 2)["n_sliced_blocks"] == 0
+    A = inputs.small_int_matrix(N, M, seed=51)
+    C0 = inputs.symmetric_uniform(N, seed=52, int_range=(-3, 3))
+    Cref = C0.copy()
+    oracle.syrk_lower(A, Cref, -1.0, 1.0)
+    il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+    dA = _dev(A)
+    ws = torch.empty(info["workspace_bytes"], dtype=torch.uint8, device="cuda")
+    for workspace in (ws, ws, False):                       # twice with the same workspace: counters are reset
+        dC = _dev(C0)
+        tb.tbs_syrk_lower(dA, dC, -1.0, 1.0, workspace=workspace)
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy()
+        assert np.array_equal(out[il], Cref[il]) and np.array_equal(out[iu], C0[iu])
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")     # too small: silently the other plan
+    dC = _dev(C0)
+    tb.tbs_syrk_lower(dA, dC, -1.0, 1.0, workspace=small)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy()[il], Cref[il])
+    Ar = inputs.normal_matrix(N, M, seed=53)
+    Cg = _run(tb, Ar, C0, 0.5, -1.5)
+    Cr, D = _reference(Ar, C0, 0.5, -1.5)
+    _check(Cg, C0, Cr, D, np.float64)
