@@ -53,14 +53,21 @@ const char* tbs_status_string(tbs_status s);
  *   A   device, N x M, lda >= max(M,1), never written
  *   C   device, N x N, ldc >= max(N,1)
  *   N, M >= 0; N == 0 is a no-op; M == 0 scales the lower triangle by beta.
- *   workspace / workspace_bytes: device scratch of at least tbs_syrk_lower_workspace() bytes
- *   (currently 0: NULL is accepted when 0 bytes are required).
+ *   workspace / workspace_bytes: optional device scratch (contents arbitrary, aligned to the
+ *   element size; owned by the caller, used only until the call's work on the stream has finished;
+ *   calls that may run at the same time need different workspaces).  tbs_syrk_lower_workspace()
+ *   reports what the library can use: 0 for most sizes.  For problems with few tiles per compute
+ *   unit it is the room for blocks that are computed in parts along the contraction dimension (the
+ *   parts are summed in a fixed order, results are reproducible).  With NULL or fewer bytes the
+ *   call is still valid: the library then uses its plan without such blocks (same results up to
+ *   the order of the floating-point sums, lower throughput).  tbs_syrk_lower_square ignores it.
  * The schedule (Section 5.1.4): C is cut into b x b tiles (b = 64); the tile rows are grouped
- * into triangle blocks R^{i,j} = { u*c + f^{i,j}(u) } of k tile rows (cyclic indexing family,
- * Section 5.1.2); one workgroup holds the k(k-1)/2 tiles of TB(R) in registers, streams the k
- * row panels of A through LDS once and uses every staged panel as left and as right operand.
- * Diagonal zones recurse, the last l tile rows and the recursion base use rectangular blocks,
- * diagonal tiles have their own code path that computes no tile above the diagonal.
+ * into triangle blocks R^{i,j} = { u*c + f^{i,j}(u) } of k tile rows (an indexing family in the
+ * sense of Section 5.1.1: the cyclic one of Section 5.1.2, or its XOR analogue for c = 2^m); one
+ * workgroup holds the k(k-1)/2 tiles of TB(R) in registers, streams the k row panels of A through
+ * LDS once and uses every staged panel as left and as right operand.  Diagonal zones recurse, the
+ * last l tile rows and the recursion base use rectangular blocks, which carry the diagonal tiles
+ * of their region (nothing above the diagonal is read or written).
  * ---------------------------------------------------------------------------------------------- */
 tbs_status tbs_syrk_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_t* bytes);
 
