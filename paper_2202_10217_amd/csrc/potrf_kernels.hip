@@ -102,30 +102,11 @@ struct PanelSteps {
 // Within a block column the operations are those of Algorithm 2 in its order; across block columns
 // the 16 products of an update are summed by the MFMA before they are subtracted, which changes
 // rounding only (integer-valued factors still come out exactly).
+// The factorisation proper, on a tile that sits in LDS (rows of kPLd elements, identity beyond nb);
+// all 256 threads call it; `fail` (meaningful in wavefront 0) receives the first failed column.
 template <typename T>
-__global__ __launch_bounds__(256) void potrf_tile_kernel(int nb, T* __restrict__ A, int64_t lda, int32_t* info,
-                                                         int32_t index0)
+__device__ __forceinline__ void factor_tile_in_lds(T* S, int nb, int& fail, int lane, int w)
 {
-    __shared__ T S[kPT * kPLd];
-    __shared__ int fail_sh;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    {
-        T v[16];
-#pragma unroll
-        for (int it = 0; it < 16; ++it) {                   // unconditional loads on clamped addresses, all
-            const int i = it * 4 + w, j = lane;             // in flight together; one row per wavefront
-            const int ic = min(i, nb - 1), jc = min(j, ic);
-            v[it] = A[(int64_t)ic * lda + jc];
-        }
-#pragma unroll
-        for (int it = 0; it < 16; ++it) {
-            const int i = it * 4 + w, j = lane;
-            S[i * kPLd + j] = (i < nb && j <= i) ? v[it] : ((i == j) ? T(1) : T(0));
-        }
-    }
-    if (tid == 0) fail_sh = -1;
-    __syncthreads();
-    int fail = -1;
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
         if (16 * kb < nb) {                                 // uniform
@@ -165,6 +146,39 @@ __global__ __launch_bounds__(256) void potrf_tile_kernel(int nb, T* __restrict__
             }
         }
     }
+}
+
+// Lower triangle of the nb x nb tile at A into LDS (identity beyond nb, zeros above the diagonal):
+// unconditional loads on clamped addresses, all in flight together; one row per wavefront and turn.
+template <typename T>
+__device__ __forceinline__ void load_lower_tile(T* S, const T* A, int64_t lda, int nb, int lane, int w)
+{
+    T v[16];
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int i = it * 4 + w, j = lane;
+        const int ic = min(i, nb - 1), jc = min(j, ic);
+        v[it] = A[(int64_t)ic * lda + jc];
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int i = it * 4 + w, j = lane;
+        S[i * kPLd + j] = (i < nb && j <= i) ? v[it] : ((i == j) ? T(1) : T(0));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void potrf_tile_kernel(int nb, T* __restrict__ A, int64_t lda, int32_t* info,
+                                                         int32_t index0)
+{
+    __shared__ T S[kPT * kPLd];
+    __shared__ int fail_sh;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    load_lower_tile(S, A, lda, nb, lane, w);
+    if (tid == 0) fail_sh = -1;
+    __syncthreads();
+    int fail = -1;
+    factor_tile_in_lds(S, nb, fail, lane, w);
     if (tid == 0 && fail >= 0) {
         fail_sh = fail;
         if (*info == 0) *info = index0 + fail + 1;
@@ -461,6 +475,106 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* 
     }
 }
 
+// ---- Cholesky of a diagonal block of up to 128 columns in one workgroup ---------------------------
+// Algorithm 5 on two tiles without leaving the compute unit: factor A11 (64 x 64), solve
+// A21 <- A21 L11^{-T}, update A22 <- A22 - A21 A21^T, factor A22 (n - 64 columns).  The three pieces are
+// the code of potrf_tile_kernel, trsm_tile_kernel and an MFMA product on tiles held in LDS; as four
+// launches they cost three kernel boundaries on the chain of every pair of tile columns.
+template <typename T>
+__global__ __launch_bounds__(256) void potrf_block_kernel(int n, T* __restrict__ A, int64_t lda, int32_t* info,
+                                                          int32_t index0)
+{
+    __shared__ T S11[kPT * kPLd], S21[kPT * kPLd], S22[kPT * kPLd];
+    __shared__ __attribute__((aligned(16))) T Lq[kPT * kLqLd];
+    __shared__ T dg[kPT], rdg[kPT];
+    __shared__ int fail_sh;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int n2 = n - kPT;                                 // 1 .. 64
+    load_lower_tile(S11, A, lda, kPT, lane, w);
+    load_lower_tile(S22, A + (int64_t)kPT * lda + kPT, lda, n2, lane, w);
+    {
+        T v[16];
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int i = it * 4 + w, j = lane;
+            v[it] = A[(int64_t)(kPT + min(i, n2 - 1)) * lda + j];
+        }
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int i = it * 4 + w, j = lane;
+            S21[i * kPLd + j] = (i < n2) ? v[it] : T(0);
+        }
+    }
+    if (tid == 0) fail_sh = -1;
+    __syncthreads();
+    int fail1 = -1, fail2 = -1;
+    factor_tile_in_lds(S11, kPT, fail1, lane, w);
+    // L11 in the layout of the substitution (see trsm_tile_kernel)
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int k = it * 4 + w, j = lane;
+        Lq[j * kLqLd + lq_perm(k)] = (j < k) ? S11[k * kPLd + j] : T(0);
+    }
+    if (tid < kPT) {
+        const T d = S11[tid * kPLd + tid];
+        dg[tid] = d;
+        rdg[tid] = T(1) / d;
+    }
+    __syncthreads();
+    {
+        const int i = tid >> 2, q = tid & 3;                // four lanes per row of A21
+        T* br = S21 + i * kPLd;
+        T b[1][16], cur[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            b[0][c] = br[8 * (c >> 1) + 2 * q + (c & 1)];
+            cur[c] = Lq[q * 16 + c];
+        }
+        TrsmSteps<T, 1, 0>::run(b, cur, dg[0], rdg[0], Lq, dg, rdg, q);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) br[8 * (c >> 1) + 2 * q + (c & 1)] = b[0][c];
+    }
+    __syncthreads();
+    {
+        int idx = 0;
+#pragma unroll
+        for (int I = 0; I < 4; ++I)
+#pragma unroll
+            for (int J = 0; J <= I; ++J) {
+                if ((idx++ & 3) == w) {                     // uniform per wavefront
+                    typename TileOps<T>::acc_t acc;
+                    T* c = S22 + (16 * I) * kPLd + 16 * J + (lane & 15);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) acc[g] = c[TileOps<T>::row_of(g, lane) * kPLd];
+                    const T* ra = S21 + (16 * I + (lane & 15)) * kPLd + (lane >> 4);
+                    const T* rb = S21 + (16 * J + (lane & 15)) * kPLd + (lane >> 4);
+#pragma unroll
+                    for (int k4 = 0; k4 < 16; ++k4) acc = TileOps<T>::mma(ra[4 * k4], -rb[4 * k4], acc);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) c[TileOps<T>::row_of(g, lane) * kPLd] = acc[g];
+                }
+            }
+    }
+    __syncthreads();
+    factor_tile_in_lds(S22, n2, fail2, lane, w);
+    if (tid == 0) {
+        const int f = (fail1 >= 0) ? fail1 : ((fail2 >= 0) ? kPT + fail2 : -1);
+        fail_sh = f;
+        if (f >= 0 && *info == 0) *info = index0 + f + 1;
+    }
+    __syncthreads();
+    // write back the columns that were finished (all of them when nothing failed)
+    const int failed = fail_sh;
+    const int ncol = (failed >= 0) ? failed : n;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int i = it * 4 + w, j = lane;
+        if (j <= i && j < ncol) A[(int64_t)i * lda + j] = S11[i * kPLd + j];
+        if (i < n2 && j < ncol) A[(int64_t)(kPT + i) * lda + j] = S21[i * kPLd + j];
+        if (i < n2 && j <= i && kPT + j < ncol) A[(int64_t)(kPT + i) * lda + kPT + j] = S22[i * kPLd + j];
+    }
+}
+
 __global__ void fill_i32_kernel(int32_t* dst, int32_t value, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -509,6 +623,20 @@ hipError_t launch_trsm_tile(bool f32, int64_t m, int nb, const void* L, int64_t 
         launch_trsm_typed<float>(m, nb, L, ldl, X, ldx, stream);
     else
         launch_trsm_typed<double>(m, nb, L, ldl, X, ldx, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_potrf_block(bool f32, int n, void* A, int64_t lda, int32_t* info, int32_t index0,
+                              hipStream_t stream)
+{
+    if (n <= kPT) return launch_potrf_tile(f32, n, A, lda, info, index0, stream);
+    if (n > 2 * kPT) return hipErrorInvalidValue;
+    if (f32)
+        hipLaunchKernelGGL(potrf_block_kernel<float>, dim3(1), dim3(256), 0, stream, n, (float*)A, lda, info,
+                           index0);
+    else
+        hipLaunchKernelGGL(potrf_block_kernel<double>, dim3(1), dim3(256), 0, stream, n, (double*)A, lda, info,
+                           index0);
     return hipGetLastError();
 }
 

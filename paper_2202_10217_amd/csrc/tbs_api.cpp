@@ -195,8 +195,7 @@ struct Lbc {
     {
         if (n >= 4 * big_block) return big_block;
         if (n > 1024) return 256;
-        if (n > 256) return 128;
-        return kTile;
+        return 128;                                                     // two tiles are one kernel
     }
 
     // X = A[row0 : row0+m, col0 : col0+nb]  <-  X * L^{-T},  L = A[col0 : col0+nb, col0 : col0+nb]
@@ -228,8 +227,8 @@ struct Lbc {
     void potrf(int64_t off, int64_t n, hipStream_t st)
     {
         if (n <= 0) return;
-        if (n <= kTile) {
-            note(tbs::launch_potrf_tile(dtype == TBS_F32, (int)n, at(off, off), lda, info, (int32_t)off, st));
+        if (n <= 2 * kTile) {                                           // one or two tiles: one workgroup
+            note(tbs::launch_potrf_block(dtype == TBS_F32, (int)n, at(off, off), lda, info, (int32_t)off, st));
             return;
         }
         const int64_t B = block_for(n);
