@@ -148,7 +148,7 @@ constexpr size_t kInfoBytes = 256;                     // the workspace holds th
 // first use, default priority, kept until the process ends).
 struct LookAhead {
     hipStream_t panel = nullptr;
-    hipEvent_t column_ready = nullptr, panel_done = nullptr;
+    hipEvent_t column_ready = nullptr, panel_done = nullptr, rest_done = nullptr;
     bool ok = false;
     std::mutex enqueue;     // held while a call records into the stream and the events: calls from
 };                          // several host threads then simply follow each other on the panel stream
@@ -165,6 +165,7 @@ LookAhead* look_ahead_for_device()
         if (hipStreamCreateWithFlags(&la.panel, hipStreamNonBlocking) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&la.column_ready, hipEventDisableTiming) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&la.panel_done, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&la.rest_done, hipEventDisableTiming) != hipSuccess) return nullptr;
         la.ok = true;
     }
     return &la;
@@ -243,12 +244,13 @@ struct Lbc {
         }
     }
 
-    // Algorithm 5 at the top level with look-ahead.  The trailing update of panel p is split: first
-    // the block column of the next panel (its diagonal block by SYRK, the rows below by a product),
-    // then the rest.  As soon as the block column is up to date, the next panel's factorisation and
-    // solve (a long chain of small kernels) run on a second stream beside the rest of the update,
-    // which leaves a few compute units free for them.  The two touch disjoint parts of A: the rest of
-    // the update writes columns right of the next panel and reads the columns of panel p.
+    // Algorithm 5 at the top level with look-ahead.  The trailing update of panel p is split in three:
+    // the diagonal block of the next panel (SYRK), the rows below it (a product), the rest.  The next
+    // panel's factorisation (a long chain of small kernels) runs on a second stream: the diagonal
+    // block is updated there and factored while the caller's stream computes the product and then the
+    // rest of the update (which leaves a few compute units free); the solve of the rows below follows
+    // on the second stream once the product is done.  The streams touch disjoint parts of A: diagonal
+    // block / rows below it / columns right of the next panel; all read the columns of panel p.
     void potrf_top(int64_t N)
     {
         const int64_t B = block_for(N);
@@ -266,21 +268,28 @@ struct Lbc {
         int64_t nb = width_for(N);                                      // width of panel p
         potrf(0, nb, stream);
         trsm(nb, N - nb, 0, nb, stream);
+        note(hipEventRecord(la->rest_done, stream));
         for (int64_t c0 = 0; c0 + nb < N;) {                            // c0: first column of panel p
             const int64_t r0 = c0 + nb, rest = N - r0;                  // trailing matrix starts at r0
             const int64_t wn = width_for(rest);
             const int64_t nbn = (wn < rest) ? wn : rest;                // width of panel p + 1
             const int64_t below = rest - nbn;
-            note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, stream));
+            // panel stream: the diagonal block of panel p + 1 is brought up to date (it was last written
+            // by the previous trailing update) and factored
+            note(hipStreamWaitEvent(la->panel, la->rest_done, 0));
+            note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, la->panel));
+            potrf(r0, nbn, la->panel);
+            // caller's stream, meanwhile: the rows below that block, then the rest of the update
             if (below > 0)
                 note(tbs::launch_gemm_nt(f32, below, nbn, nb, -1.0, at(r0 + nbn, c0), lda, at(r0, c0), lda, 1.0,
                                          at(r0 + nbn, r0), lda, compute_units(), stream));
             note(hipEventRecord(la->column_ready, stream));
-            if (below > 0)                                              // the long kernel first: the host
+            if (below > 0)
                 note(syrk_impl(false, dtype, below, nb, -1.0, at(r0 + nbn, c0), lda, 1.0, at(r0 + nbn, r0 + nbn),
-                               lda, stream, reserve_units));            // needs a while to queue the chain
+                               lda, stream, reserve_units));
+            note(hipEventRecord(la->rest_done, stream));
+            // panel stream: the solve of the rows below needs them up to date
             note(hipStreamWaitEvent(la->panel, la->column_ready, 0));
-            potrf(r0, nbn, la->panel);
             if (below > 0) trsm(r0 + nbn, below, r0, nbn, la->panel);
             note(hipEventRecord(la->panel_done, la->panel));
             note(hipStreamWaitEvent(stream, la->panel_done, 0));
