@@ -54,6 +54,9 @@ TYPES = {
 }
 
 TMP_BASE = 128                   # first vector register the loop uses as scratch (declared clobbered)
+GR_N = 92                        # scalar registers s[92:93], s[94:95]: the moving row-side / column-side pointers
+GQ_N = 94
+GR, GQ = f"s[{GR_N}:{GR_N + 1}]", f"s[{GQ_N}:{GQ_N + 1}]"
 
 
 def vreg(first, n):
@@ -87,25 +90,33 @@ def gen(ty, shape_name, slots_mask):
     CB = npu * PANEL_BYTES
     NBUF = min(MAX_BUFS, LDS_RING_BYTES // CB)
     RING = NBUF * CB
+    NSEG = (RING + 65535) // 65536                          # 64 KB segments an offset field can span
     LPC = 2 * npu                                           # loads per wavefront and chunk
+    uses_q = any(S["col_side"](p) for p in panels)
+    uses_r = any(not S["col_side"](p) for p in panels)
     pieces = [("a", i, rb) for i in a_used for rb in range(4)] + [("b", j) for j in b_used]
     n_op, opr = len(pieces), T["opregs"]
     set_base = [TMP_BASE, TMP_BASE + n_op * opr]
-    ad_base = TMP_BASE + 2 * n_op * opr                     # KS row-side + KS column-side addresses
-    last_tmp = ad_base + 2 * KS - 1
+    ad_base = TMP_BASE + 2 * n_op * opr                     # per segment: KS row-side + KS column-side addresses
+    last_tmp = ad_base + NSEG * 2 * KS - 1
+    assert last_tmp < 256
 
     def op_reg(setno, piece):
         return vreg(set_base[setno] + pieces.index(piece) * opr, opr)
 
-    def rd_instr(setno, piece, ks):
+    def rd_instr(setno, piece, buf, ks):
+        """Read of an operand piece of k-step ks from ring buffer buf: the address register of the
+        64 KB segment the byte lies in, the rest in the offset field."""
         if piece[0] == "a":
-            off = sp[S["a"][piece[1]]] * PANEL_BYTES + piece[2] * RB_BYTES
-            return f"{T['rd']} {op_reg(setno, piece)}, v{ad_base + ks} offset:{off}"
-        off = sp[S["b"][piece[1]]] * PANEL_BYTES
-        return f"{T['rd']} {op_reg(setno, piece)}, v{ad_base + KS + ks} offset:{off}"
+            off = buf * CB + sp[S["a"][piece[1]]] * PANEL_BYTES + piece[2] * RB_BYTES
+            reg = ad_base + (off >> 16) * 2 * KS + ks
+        else:
+            off = buf * CB + sp[S["b"][piece[1]]] * PANEL_BYTES
+            reg = ad_base + (off >> 16) * 2 * KS + KS + ks
+        return f"{T['rd']} {op_reg(setno, piece)}, v{reg} offset:{off & 0xFFFF}"
 
-    def reads(setno, ks):
-        return [rd_instr(setno, pc, ks) for pc in pieces]
+    def reads(setno, buf, ks):
+        return [rd_instr(setno, pc, buf, ks) for pc in pieces]
 
     def mfmas(setno):
         out = []
@@ -115,75 +126,81 @@ def gen(ty, shape_name, slots_mask):
                 out.append(f"{T['mfma']} {acc}, {op_reg(setno, ('a', i, rb))}, {op_reg(setno, ('b', j))}, {acc}")
         return out
 
-    def set_addresses():
-        """LDS addresses of the buffer at ring offset %[cb] into the working address registers."""
-        out = [f"v_add_u32 v{ad_base + j}, %[cb], %[ada{j}]" for j in range(KS)]
-        out += [f"v_add_u32 v{ad_base + KS + j}, %[cb], %[adb{j}]" for j in range(KS)]
-        return out
-
-    def issue():
-        """Request chunk %[ci] into the ring buffer at %[ib]; advance both (the caller has checked
-        that the chunk exists)."""
-        out = ["s_add_u32 %[tmp], %[m0b], %[ib]"]
+    def issue(buf):
+        """Request the next chunk into ring buffer buf and move the matrix pointers one chunk on."""
+        out = []
         for q in range(LPC):
             p, h = panels[q // 2], q % 2
-            base = "%[gQ]" if S["col_side"](p) else "%[gR]"
-            out += [f"s_add_u32 m0, %[tmp], {sp[p] * PANEL_BYTES + h * HALF_BYTES}", "s_nop 0",
-                    f"global_load_lds_dwordx4 %[go{q}], {base}",
-                    f"v_add_u32 %[go{q}], %[step], %[go{q}]"]
-        out += ["s_add_u32 %[ci], %[ci], 1", f"s_add_u32 %[ib], %[ib], {CB}", f"s_cmp_eq_u32 %[ib], {RING}",
-                "s_cselect_b32 %[ib], 0, %[ib]"]
+            base = GQ if S["col_side"](p) else GR
+            out += [f"s_add_u32 m0, %[m0b], {buf * CB + sp[p] * PANEL_BYTES + h * HALF_BYTES}", "s_nop 0",
+                    f"global_load_lds_dwordx4 %[go{q}], {base}"]
+        for used, base in ((uses_r, GR_N), (uses_q, GQ_N)):
+            if used:
+                out += [f"s_add_u32 s{base}, s{base}, %[step]", f"s_addc_u32 s{base + 1}, s{base + 1}, 0"]
         return out
 
     L = []
     # ---- prologue: request the first min(NBUF, nch) chunks, wait for chunk 0 --------------------
-    L += ["s_mov_b32 %[cnt], 0", "s_mov_b32 %[ci], 0", "s_mov_b32 %[ib], 0", "s_mov_b32 %[cb], 0"]
+    L += [f"s_mov_b64 {GR}, %[gR]", f"s_mov_b64 {GQ}, %[gQ]", "s_mov_b32 %[cnt], 0"]
     for n in range(NBUF):
-        L += ["s_cmp_lt_u32 %[ci], %[nch]", f"s_cbranch_scc0 10f"] + issue()
-    L += ["10:"]
+        # (a scalar register written by the scalar unit may be read by a memory instruction 5 wait
+        # states later at the earliest: the moved pointers, also after the s_mov_b64 above)
+        L += [f"s_cmp_lt_u32 %[cnt], %[nch]", "s_cbranch_scc0 10f", "s_nop 4"] + issue(n) + ["s_add_u32 %[cnt], %[cnt], 1"]
+    L += ["10:", "s_mov_b32 %[cnt], 0"]
     # all NBUF requested: chunk 0 has landed when at most (NBUF-1)*LPC loads are outstanding;
     # fewer chunks than buffers: wait for everything
     L += [f"s_cmp_ge_u32 %[nch], {NBUF}", "s_cbranch_scc1 11f", "s_waitcnt vmcnt(0)", "11:",
           f"s_waitcnt vmcnt({(NBUF - 1) * LPC})", "s_barrier"]
-    L += set_addresses()
-    L += reads(0, 0)
-    # ---- the loop ----------------------------------------------------------------------------------
+    for seg in range(1, NSEG):                              # address registers of the upper segments
+        for j in range(KS):
+            L += [f"v_add_u32 v{ad_base + seg * 2 * KS + j}, {seg * 65536}, %[ada{j}]",
+                  f"v_add_u32 v{ad_base + seg * 2 * KS + KS + j}, {seg * 65536}, %[adb{j}]"]
+    for j in range(KS):
+        L += [f"v_mov_b32 v{ad_base + j}, %[ada{j}]", f"v_mov_b32 v{ad_base + KS + j}, %[adb{j}]"]
+    L += reads(0, 0, 0)
+    # ---- the loop: one pass over the ring per iteration ------------------------------------------
     L += ["1:"]
-    for ks in range(KS - 1):
-        L += ["s_waitcnt lgkmcnt(0)"]
-        L += spread(mfmas(ks & 1), reads((ks + 1) & 1, ks + 1))
-    # next chunk landed (this wavefront's part), all LDS reads of this buffer returned
-    L += [f"s_add_u32 %[tmp], %[cnt], {NBUF}", "s_cmp_le_u32 %[tmp], %[nch]", "s_cbranch_scc1 12f",
-          "s_waitcnt vmcnt(0)", "12:", f"s_waitcnt vmcnt({(NBUF - 2) * LPC}) lgkmcnt(0)", "s_barrier"]
-    L += [f"s_add_u32 %[cb], %[cb], {CB}", f"s_cmp_eq_u32 %[cb], {RING}", "s_cselect_b32 %[cb], 0, %[cb]"]
-    last = mfmas((KS - 1) & 1)
-    common = set_addresses() + reads(0, 0)
-    L += ["s_cmp_lt_u32 %[ci], %[nch]", "s_cbranch_scc0 2f"]
-    L += spread(last, common + issue())
-    L += ["s_branch 3f", "2:"]
-    L += spread(last, common)
-    L += ["3:", "s_add_u32 %[cnt], %[cnt], 1", "s_cmp_lt_u32 %[cnt], %[nch]", "s_cbranch_scc1 1b"]
+    tails = []                                              # rarely executed pieces, placed after the loop
+    for buf in range(NBUF):
+        nxt = (buf + 1) % NBUF
+        for ks in range(KS - 1):
+            L += ["s_waitcnt lgkmcnt(0)"]
+            L += spread(mfmas(ks & 1), reads((ks + 1) & 1, buf, ks + 1))
+        # The next chunk has landed (this wavefront's part) when, of the NBUF - 1 chunks requested
+        # after it, all but the oldest... are still outstanding; near the end fewer are: wait for all.
+        L += [f"s_add_u32 %[tmp], %[cnt], {NBUF}", "s_cmp_le_u32 %[tmp], %[nch]", f"s_cbranch_scc0 {20 + buf}f",
+              f"s_waitcnt vmcnt({(NBUF - 2) * LPC}) lgkmcnt(0)", f"{40 + buf}:", "s_barrier"]
+        tails += [f"{20 + buf}:", "s_waitcnt vmcnt(0) lgkmcnt(0)", f"s_branch {40 + buf}b"]
+        last = mfmas((KS - 1) & 1)
+        first_reads = reads(0, nxt, 0)
+        # chunk cnt + NBUF goes into the buffer just freed, if it exists
+        L += ["s_cmp_lt_u32 %[tmp], %[nch]", f"s_cbranch_scc0 {60 + buf}f"]
+        L += spread(last, first_reads + issue(buf))
+        L += [f"{80 + buf}:", "s_add_u32 %[cnt], %[cnt], 1", "s_cmp_lt_u32 %[cnt], %[nch]", "s_cbranch_scc0 4f"]
+        tails += [f"{60 + buf}:"] + spread(last, first_reads) + [f"s_branch {80 + buf}b"]
+    L += ["s_branch 1b"]
+    L += tails
     # ---- drain ----------------------------------------------------------------------------------
-    L += ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_nop 15", "s_nop 15"]
+    L += ["4:", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_nop 15", "s_nop 15"]
 
     text = "\n".join(f'        "{line}\\n\\t"' for line in L)
     accs = ", ".join(f'[c{n}_{rb}] "+a"(acc[{n}][{rb}])' for n, _ in slots for rb in range(4))
-    gos = ", ".join(f'[go{q}] "+v"(go[{q}])' for q in range(LPC))
+    gos = ", ".join(f'[go{q}] "v"(go[{q}])' for q in range(LPC))
     ads = ", ".join(f'[ada{j}] "v"(g.ada[{j}]), [adb{j}] "v"(g.adb[{j}])' for j in range(KS))
-    clob = ", ".join(f'"v{r}"' for r in range(TMP_BASE, last_tmp + 1))
+    clob = ", ".join([f'"v{r}"' for r in range(TMP_BASE, last_tmp + 1)] + [f'"s{r}"' for r in range(GR_N, GR_N + 4)])
     name = f"asm_loop_{ty}_{shape_name}_{slots_mask:02x}"
     fn = f"""
 // {ty}, {shape_name} block, slots 0x{slots_mask:02x}: panels {panels}, ring of {NBUF} chunk buffers of {CB} bytes,
 // {len(slots) * 4} MFMAs and {n_op} operand reads per k-step, {LPC} loads per wavefront and chunk
-__device__ __forceinline__ void {name}(Cfg<{ty}>::acc_t (&acc)[6][4], const AsmLoopArgs& g, uint32_t (&go)[10])
+__device__ __forceinline__ void {name}(Cfg<{ty}>::acc_t (&acc)[6][4], const AsmLoopArgs& g, const uint32_t (&go)[10])
 {{
-    uint32_t cnt, tmp, ci, ib, cb;
+    uint32_t cnt, tmp;
     asm volatile(
 {text}
         : {accs},
-          {gos},
-          [cnt] "=&s"(cnt), [tmp] "=&s"(tmp), [ci] "=&s"(ci), [ib] "=&s"(ib), [cb] "=&s"(cb)
-        : {ads},
+          [cnt] "=&s"(cnt), [tmp] "=&s"(tmp)
+        : {gos},
+          {ads},
           [gR] "s"(g.gR), [gQ] "s"(g.gQ), [nch] "s"(g.nch), [step] "s"(g.step), [m0b] "s"(g.m0base)
         : "memory", "scc", {clob});
 }}
@@ -204,7 +221,7 @@ def main():
     for ty, shape_name, mask, name in table:
         out.append(f"template <> struct AsmLoop<{ty}, {shape_name}Shape, 0x{mask:02x}u> {{\n"
                    f"    static __device__ __forceinline__ void run(Cfg<{ty}>::acc_t (&acc)[6][4], "
-                   f"const AsmLoopArgs& g, uint32_t (&go)[10]) {{ {name}(acc, g, go); }}\n}};\n")
+                   f"const AsmLoopArgs& g, const uint32_t (&go)[10]) {{ {name}(acc, g, go); }}\n}};\n")
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "syrk_asm_loops.inc")
     with open(path, "w") as f:
         f.write("".join(out))
