@@ -55,7 +55,16 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
     auto it = cache.find(key);
     if (it == cache.end()) {
         const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
-        const double overhead_tiles = 20.0 / tile_us;
+        // (TBS_PLAN_COSTS="block_us,slice_us" overrides the two fixed costs, for measurements)
+        double block_us = 20.0, slice_us = 0.03 * tile_us;
+        if (const char* c = std::getenv("TBS_PLAN_COSTS")) {
+            double b = 0.0, sl = 0.0;
+            if (std::sscanf(c, "%lf,%lf", &b, &sl) == 2 && b >= 0.0 && sl >= 0.0) {
+                block_us = b;
+                slice_us = sl;
+            }
+        }
+        const double overhead_tiles = block_us / tile_us;
         tbs::Plan p;
         // TBS_PLAN_FAMILY=cyclic: the paper's cyclic family only (no power-of-two moduli)
         const char* famenv = std::getenv("TBS_PLAN_FAMILY");
@@ -83,7 +92,8 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
                 tbs::Plan q;
                 if (tbs::apply_slicing(p, tbs::Slicing{st, sr, tb, ts}, &q)) p = q;
             }
-        } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family, max_slices)) {
+        } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family, max_slices,
+                                     slice_us / tile_us)) {
             return nullptr;
         }
         it = cache.emplace(key, p).first;

@@ -195,7 +195,7 @@ bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
     return true;
 }
 
-double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
+double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles)
 {
     std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
     for (int32_t u = 0; u < ncu; ++u) free_at.push(0.0);
@@ -218,7 +218,7 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
         } else {
             continue;                                       // empty block: exits at once
         }
-        if (it.slices > 1) tiles = tiles / it.slices + 0.03;   // plus its share of summing the parts
+        if (it.slices > 1) tiles = tiles / it.slices + slice_overhead_tiles;   // plus storing / summing the parts
         const double start = free_at.top();
         free_at.pop();
         const double stop = start + tiles + overhead_tiles;
@@ -229,7 +229,7 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles)
 }
 
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family,
-                 int32_t max_slices)
+                 int32_t max_slices, double slice_overhead_tiles)
 {
     if (square) return build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out);
     PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
@@ -238,7 +238,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     // with many blocks per compute unit the granularity of the tail does not matter
     const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
     if (per_unit > 200.0 || T < 2) return true;
-    double best = simulate_makespan(*out, ncu, overhead_tiles);
+    double best = simulate_makespan(*out, ncu, overhead_tiles, slice_overhead_tiles);
     // cutting blocks along the contraction dimension costs a workspace and an extra pass over the
     // parts: only for problems with few tiles per compute unit, and only for a clear gain
     const bool slicing = max_slices > 1 && per_unit <= 40.0;
@@ -257,7 +257,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
                     if (!apply_slicing(base, Slicing{st, sr, tl[0], tl[1]}, &q)) continue;
                     // at most 128 MB of workspace (6 tiles of doubles per part)
                     if ((int64_t)q.n_ws_blocks * q.ws_slices * 6 * kTile * kTile * 8 > ((int64_t)128 << 20)) continue;
-                    const double span = simulate_makespan(q, ncu, overhead_tiles);
+                    const double span = simulate_makespan(q, ncu, overhead_tiles, slice_overhead_tiles);
                     if (span < best_sliced * 0.995) {
                         best_sliced = span;
                         sliced = q;
@@ -274,7 +274,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
                 tune.xor_family = xor_family;
                 Plan cand;
                 if (!build_plan(T, tune, &cand)) continue;
-                const double span = simulate_makespan(cand, ncu, overhead_tiles);
+                const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles);
                 if (span < best * 0.98) {                   // prefer the coarser plan on near ties
                     best = span;
                     *out = cand;
