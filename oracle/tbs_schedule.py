@@ -7,7 +7,9 @@ Nothing here is used by the GPU path.  It serves three purposes in the tests:
   * it counts the elements the schedule loads, for comparison with the cost
     formulas of Section 5.1.3 / 5.1.4 (Q1 = c^2 k b M, C loaded once);
   * it lists the triangle blocks of every recursion level, which pins the index
-    arithmetic of the GPU library's planner.
+    arithmetic of the GPU library's planner;
+  * it replays Large Block Cholesky (Section 5.2.1, Algorithm 5) with that scheme as
+    trailing update and counts the update's loads (terms (3) and (4) of Section 5.2.2).
 It also holds the closed forms of Sections 3.2, 4.1, 4.2 and 5.2.2.
 
 Readings of the paper taken here (the text is ambiguous or silent):
@@ -216,6 +218,39 @@ def tbs_syrk(A: np.ndarray, C: np.ndarray, k: int, b: int = 1, s: int = None,
             for u in range(k):
                 for v in range(u):
                     _update_pair(A, C, tiles[u], tiles[v], alpha)
+    return io
+
+
+# ----------------------------------------------------------------------------
+# Section 5.2.1, Algorithm 5: Large Block Cholesky
+# ----------------------------------------------------------------------------
+
+
+def lbc_cholesky(S: np.ndarray, b: int, k: int, tile: int = 1, io: IOCount = None, families: str = "cyclic") -> IOCount:
+    """Algorithm 5, in place on the lower triangle of S: for every block of b columns, the Cholesky
+    factor of the diagonal block, the triangular solve of the block column below it, and the
+    trailing update C <- C - X X^T by the Triangle Block Scheme (tbs_syrk with alpha = -1).
+
+    The paper cites the first two steps (OOC_CHOL, OOC_TRSM) without spelling them out; they are
+    done here by Algorithm 2's own operations (column by column), and their loads are not counted:
+    `io` receives the loads of the trailing updates only (terms (3) and (4) of Section 5.2.2), per
+    panel in io.per_panel as (rows of the trailing matrix, A elements, C elements).
+    Ranges are half-open and the last block may be narrower (the paper assumes b | N)."""
+    if io is None:
+        io = IOCount()
+    io.per_panel = []
+    N = S.shape[0]
+    for i0 in range(0, N, b):
+        i1 = min(i0 + b, N)
+        for j in range(i0, i1):                         # A[I0, I0] <- CHOL, A[I1, I0] <- TRSM: Algorithm 2
+            S[j, j] = math.sqrt(S[j, j])                # restricted to the columns of the block
+            S[j + 1:, j] /= S[j, j]
+            for jj in range(j + 1, i1):
+                S[jj:, jj] -= S[jj:, j] * S[jj, j]
+        if i1 < N:
+            a0, c0 = io.A, io.C
+            tbs_syrk(S[i1:, i0:i1], S[i1:, i1:], k, tile, alpha=-1.0, io=io, families=families)
+            io.per_panel.append((N - i1, io.A - a0, io.C - c0))
     return io
 
 

@@ -227,3 +227,59 @@ def test_relaxed_optimum_closed_forms():
     # with X = 3S the bound gives operational intensity sqrt(S/2) (corollary of Section 4.1)
     S = 1234.0
     assert abs(ts.H_max_bound(3 * S) / (2 * S) - math.sqrt(S / 2)) < 1e-9
+
+
+# ---- Algorithm 5 (Large Block Cholesky) replayed ---------------------------------------------------
+def _integer_factor(N, seed):
+    rng = np.random.default_rng(seed)
+    G = np.tril(rng.integers(-2, 3, size=(N, N))).astype(np.float64)
+    G[np.diag_indices(N)] = rng.integers(1, 4, size=N)
+    return G
+
+
+@pytest.mark.parametrize("N,b,k,tile", [(48, 8, 3, 1), (96, 16, 4, 2), (100, 24, 4, 2), (130, 32, 5, 1), (64, 64, 4, 2)])
+def test_lbc_recovers_an_integer_factor_exactly(N, b, k, tile):
+    """Uniqueness of the Cholesky factor: S = G G^T with an integer G of positive diagonal gives back G,
+    bit for bit (every intermediate value is an integer), whatever the block sizes, ragged ones included."""
+    G = _integer_factor(N, 5)
+    S = G @ G.T
+    upper = np.triu_indices(N, 1)
+    S[upper] = -77.0                                    # never read, never written
+    ts.lbc_cholesky(S, b, k, tile)
+    assert np.array_equal(np.tril(S), G)
+    assert np.all(S[upper] == -77.0)
+
+
+def test_lbc_equals_algorithm_2_on_a_random_matrix():
+    import oracle
+    rng = np.random.default_rng(11)
+    N = 120
+    X = rng.standard_normal((N, N))
+    S = X @ X.T + N * np.eye(N)
+    L_ref = S.copy()
+    assert oracle.potrf_lower(L_ref) == 0
+    L = S.copy()
+    ts.lbc_cholesky(L, 24, 4, 2, families="auto")
+    assert np.max(np.abs(np.tril(L) - np.tril(L_ref))) <= 1e-12 * np.max(np.abs(L_ref))
+
+
+def test_lbc_volume_terms():
+    """Section 5.2.2: every trailing update loads its C once, n(n+1)/2 elements for n rows (summing to the
+    N^3/(6b) term), and its A volume follows the tiled TBS leading term n^2 b/((k-1) tile), the excess
+    shrinking as the trailing matrix grows."""
+    k, tile, b = 4, 4, 32
+    N = 768
+    S = _integer_factor(N, 3)
+    S = S @ S.T
+    io = ts.lbc_cholesky(S, b, k, tile)
+    assert len(io.per_panel) == N // b - 1
+    for n, a_elems, c_elems in io.per_panel:
+        assert c_elems == n * (n + 1) // 2
+    total_c = sum(c for _, _, c in io.per_panel)
+    assert abs(total_c / (N ** 3 / (6.0 * b)) - 1.0) < 0.08
+    ratios = [(n, a / ts.tiled_tbs_A_leading(n, b, k, tile)) for n, a, _ in io.per_panel if n >= 4 * k * tile]
+    assert all(0.9 < r < 2.2 for _, r in ratios)
+    big = [r for n, r in ratios if n >= 512]
+    small = [r for n, r in ratios if n <= 192]
+    assert max(big) < min(small)                        # lower-order terms fade with the size
+    assert max(big) < 1.35
