@@ -46,7 +46,9 @@ SHAPES = {
     "Rect": dict(a=[3, 4], b=[0, 1, 2],
                  slots=[(0, 0), (0, 1), (0, 2), (1, 0), (1, 1), (1, 2)], col_side=lambda p: p < 3),
 }
-FAST_SETS = {"Tri": [0x3F, 0x07, 0x01], "Rect": [0x3F, 0x1B, 0x09, 0x07, 0x03, 0x01]}
+# Rect: the full 2 x 3 block and its sub-rectangles, then the three sets a two-row block can be left with
+# when it straddles the diagonal (0x3B, 0x19, 0x08: the first row loses its last one or two tiles / is empty)
+FAST_SETS = {"Tri": [0x3F, 0x07, 0x01], "Rect": [0x3F, 0x1B, 0x09, 0x07, 0x03, 0x01, 0x3B, 0x19, 0x08]}
 
 TYPES = {
     "double": dict(ks=4, rd="ds_read_b64", mfma="v_mfma_f64_16x16x4_f64", opregs=2),

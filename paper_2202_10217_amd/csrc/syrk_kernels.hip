@@ -564,17 +564,19 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
 }
 
 // The slot sets that have a branch-free instance: a triangle block on 4, 3 or 2 tile rows; a
-// rectangle of r x c tiles, r <= 2, c <= 3.
+// rectangle of r x c tiles, r <= 2, c <= 3; a two-row rectangle that straddles the diagonal (its
+// first row without its last tile, without its last two tiles of three or two, or empty).
 template <class Shape> struct FastSets;
 template <> struct FastSets<TriShape> {
     static constexpr int N = 3;
     static constexpr uint32_t set(int n) { return n == 0 ? 0x3Fu : n == 1 ? 0x07u : 0x01u; }
 };
 template <> struct FastSets<RectShape> {
-    static constexpr int N = 6;
+    static constexpr int N = 9;
     static constexpr uint32_t set(int n)
     {
-        return n == 0 ? 0x3Fu : n == 1 ? 0x1Bu : n == 2 ? 0x09u : n == 3 ? 0x07u : n == 4 ? 0x03u : 0x01u;
+        return n == 0 ? 0x3Fu : n == 1 ? 0x1Bu : n == 2 ? 0x09u : n == 3 ? 0x07u : n == 4 ? 0x03u : n == 5 ? 0x01u
+             : n == 6 ? 0x3Bu : n == 7 ? 0x19u : 0x08u;
     }
 };
 

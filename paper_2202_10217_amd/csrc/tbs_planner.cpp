@@ -57,11 +57,10 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
         int64_t nz = 1;
         for (;;) {
             const int32_t mr = tune.mr, nc = tune.nc;       // rectangles left of a zone
-            // rectangles of a triangular region: their own shape, one tile row high when they carry
-            // the diagonal tiles (a block that straddles the diagonal then lacks only trailing
-            // tiles, which every code path handles at full speed)
+            // rectangles of a triangular region: their own shape if one is given (a block that
+            // straddles the diagonal keeps the tiles on and below it)
             const bool own = tune.mr_deep > 0 && tune.nc_deep > 0;
-            const int32_t mrt = with_diag ? 1 : (own ? tune.mr_deep : tune.mr);
+            const int32_t mrt = own ? tune.mr_deep : tune.mr;
             const int32_t nct = own ? tune.nc_deep : tune.nc;
             int32_t c = choose_c(Tl / k, k), fam = 0;
             if (tune.xor_family && Tl / k >= 4) {
@@ -231,7 +230,24 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, doub
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family,
                  int32_t max_slices, double slice_overhead_tiles)
 {
-    if (square) return build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out);
+    if (square) {
+        // rectangles only; for small matrices the block shape with the shortest simulated makespan
+        // (the same rule as below, so that the baseline is not handicapped by coarse blocks)
+        if (!build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out)) return false;
+        if (0.5 * (double)T * (double)T / (double)std::max(ncu, 1) > 200.0 || T < 2) return true;
+        double best_sq = simulate_makespan(*out, ncu, overhead_tiles, slice_overhead_tiles);
+        const int32_t sq_shapes[4][2] = {{2, 2}, {1, 3}, {1, 2}, {1, 1}};
+        for (const auto& sh : sq_shapes) {
+            Plan cand;
+            if (!build_plan(T, PlanTuning{0, sh[0], sh[1], false}, &cand)) continue;
+            const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles);
+            if (span < best_sq * 0.98) {
+                best_sq = span;
+                *out = cand;
+            }
+        }
+        return true;
+    }
     PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
     coarse.xor_family = xor_family;
     if (!build_plan(T, coarse, out)) return false;
@@ -269,18 +285,19 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     const int32_t shapes[5][2] = {{2, 3}, {2, 2}, {1, 3}, {1, 2}, {1, 1}};
     for (int32_t levels = kMaxLevels; levels >= 0; levels = (levels == kMaxLevels) ? 2 : levels - 1) {
         for (const auto& sh : shapes) {
-            for (int32_t nct = kRectCols; nct >= 1; --nct) {    // triangular regions: 1 x nct blocks
-                PlanTuning tune{levels, sh[0], sh[1], false, 1, nct};
-                tune.xor_family = xor_family;
-                Plan cand;
-                if (!build_plan(T, tune, &cand)) continue;
-                const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles);
-                if (span < best * 0.98) {                   // prefer the coarser plan on near ties
-                    best = span;
-                    *out = cand;
+            for (int32_t mrt = kRectRows; mrt >= 1; --mrt)      // triangular regions: mrt x nct blocks
+                for (int32_t nct = kRectCols; nct >= 1; --nct) {
+                    PlanTuning tune{levels, sh[0], sh[1], false, mrt, nct};
+                    tune.xor_family = xor_family;
+                    Plan cand;
+                    if (!build_plan(T, tune, &cand)) continue;
+                    const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles);
+                    if (span < best * 0.98) {               // prefer the coarser plan on near ties
+                        best = span;
+                        *out = cand;
+                    }
+                    if (slicing && sh[0] == 1 && mrt == 1) try_slicings(cand);
                 }
-                if (slicing && sh[0] == 1) try_slicings(cand);
-            }
         }
     }
     if (have_sliced && best_sliced < best * 0.97) *out = sliced;

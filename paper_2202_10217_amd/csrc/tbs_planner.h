@@ -37,7 +37,8 @@ bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out);
 // the descriptor.
 bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
 
-// The plan the library uses.  square = true: rectangular 2 x 3 blocks only (the baseline).
+// The plan the library uses.  square = true: rectangular blocks only (the baseline): 2 x 3 tiles, smaller
+// ones for small matrices by the rule below.
 // Otherwise the schedule of Algorithm 4; for small matrices, where a compute unit receives only a
 // few blocks, the candidates differ in how finely the diagonal zones and the last tile rows are cut,
 // and the one with the shortest simulated makespan on `ncu` compute units is taken (blocks are
