@@ -85,7 +85,7 @@ def test_every_lower_tile_exactly_once(N, M, square):
 
 
 TUNINGS = ["0,2,3,0", "0,1,1,0", "1,2,3,0,1,3", "1,1,3,0,1,2", "1,2,2,0,1,1", "2,1,2,0,1,3", "10,2,3,1",
-           "10,2,3,0,1,3", "10,1,1,0,1,1", "2,2,3,1"]
+           "10,2,3,0,1,3", "10,1,1,0,1,1", "2,2,3,1", "1,2,3,0,2,3", "2,2,2,0,2,2", "1,1,3,0,2,1"]
 
 
 @pytest.mark.parametrize("idx", range(len(TUNINGS)))

@@ -314,3 +314,29 @@ def test_blocks_cut_along_the_contraction_dimension(tb, N, M):
     Cg = _run(tb, Ar, C0, 0.5, -1.5)
     Cr, D = _reference(Ar, C0, 0.5, -1.5)
     _check(Cg, C0, Cr, D, np.float64)
+
+
+# block shapes pinned through the environment ("levels,rows,cols,base,zone_rows,zone_cols"): among them
+# two-row rectangles in triangular regions, whose blocks straddle the diagonal in three different ways;
+# one size per tuning because the library keeps one plan per size
+PINNED = ["0,2,3,0", "1,2,3,0,2,3", "2,2,2,0,2,2", "1,1,3,0,2,1", "1,2,3,0,1,2", "10,2,3,1"]
+
+
+@pytest.mark.parametrize("idx", range(len(PINNED)))
+def test_pinned_block_shapes_bit_exact_and_in_tolerance(tb, idx, monkeypatch):
+    monkeypatch.setenv("TBS_PLAN_TUNING", PINNED[idx])
+    for N, M in ((1216 + 64 * idx, 48), (1500 + 64 * idx + 7, 80)):     # whole tiles; a ragged last tile
+        A = inputs.small_int_matrix(N, M, seed=30 + idx, dtype=np.float64)
+        C0 = inputs.symmetric_uniform(N, seed=40 + idx, dtype=np.float64, int_range=(-9, 9))
+        Cg = _run(tb, A, C0, -1.0, 1.0)
+        Cref = C0.copy()
+        oracle.syrk_lower(A, Cref, -1.0, 1.0)
+        il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+        assert np.array_equal(Cg[il], Cref[il])
+        assert np.array_equal(Cg[iu], C0[iu])
+    N, M = 1088 + 64 * idx, 64
+    A = inputs.normal_matrix(N, M, 50 + idx, 1.0, np.float64)
+    C0 = inputs.symmetric_uniform(N, 60 + idx, dtype=np.float64)
+    Cg = _run(tb, A, C0, -1.0, 1.0)
+    Cref, D = _reference(A, C0, -1.0, 1.0)
+    _check(Cg, C0, Cref, D, np.float64)
