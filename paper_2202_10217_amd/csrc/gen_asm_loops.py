@@ -26,6 +26,18 @@ Schedule per chunk (KS = KC/4 k-steps, one MFMA per accumulator and k-step):
         request of chunk (current + NBUF) into the buffer just freed
 The prologue requests the first NBUF chunks, waits for chunk 0 and reads its first operands.
 
+No vector ALU instruction between the MFMAs.  A `v_add_u32` issued while the MFMA pipeline is busy
+costs about 13 cycles of MFMA time (measured: a loop that recomputed 8 LDS addresses and 8 global
+offsets per chunk ran a k-step of 4 / 24 fp64 MFMAs in 322 / 1591 cycles instead of 256 / 1536; LDS
+reads, waits, scalar instructions and the barrier are free).  Hence:
+  - one iteration of the loop is one pass over the whole ring, so the position of a buffer is a
+    constant: operand reads carry it in their offset field (16 bits; one set of address registers
+    per 64 KB of the ring, set up once), the LDS target of a load is a constant added to M0;
+  - the lanes' global offsets never change; the scalar unit moves the two matrix pointers one chunk
+    on after each request (copies in fixed scalar registers, declared clobbered);
+  - rarely executed code (the waits near the end, the last k-step without a request) sits after the
+    loop, so the steady state takes no branch except the back edge once per pass.
+
 Hazards kept by construction: two MFMAs on one accumulator are separated by the MFMAs of all other
 accumulators (>= 3 instructions of 16 (fp64) / 8 (fp32) passes, more than the required distance);
 operand registers are double buffered, so an LDS read never overwrites what an MFMA in flight still
