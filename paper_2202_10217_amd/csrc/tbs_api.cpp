@@ -154,11 +154,13 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
 // ---- Large Block Cholesky ------------------------------------------------------------------------
 constexpr size_t kInfoBytes = 256;                     // the workspace holds the info word only
 
-// A second stream and two events per device for the look-ahead of Large Block Cholesky (created on
+// Two more streams and a few events per device for the look-ahead of Large Block Cholesky (created on
 // first use, default priority, kept until the process ends).
+constexpr int kSolvePieces = 8;
 struct LookAhead {
-    hipStream_t panel = nullptr;
+    hipStream_t panel = nullptr, solve = nullptr;
     hipEvent_t column_ready = nullptr, panel_done = nullptr, rest_done = nullptr;
+    hipEvent_t block_done[kSolvePieces] = {};
     bool ok = false;
     std::mutex enqueue;     // held while a call records into the stream and the events: calls from
 };                          // several host threads then simply follow each other on the panel stream
@@ -173,6 +175,9 @@ LookAhead* look_ahead_for_device()
     LookAhead& la = per_device[dev];
     if (!la.ok) {
         if (hipStreamCreateWithFlags(&la.panel, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        if (hipStreamCreateWithFlags(&la.solve, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        for (auto& e : la.block_done)
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&la.column_ready, hipEventDisableTiming) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&la.panel_done, hipEventDisableTiming) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&la.rest_done, hipEventDisableTiming) != hipSuccess) return nullptr;
@@ -196,6 +201,7 @@ struct Lbc {
     // better use of the few compute units the panel stream has next to a long trailing update.
     int64_t fused_trsm_rows = 6144;
     int64_t wide_rows = 8192;   // trailing matrices at least this tall get double-width panels
+    bool piecewise_solve = true;   // narrow panels: solve of the rows below block by block on a third stream
     hipError_t err = hipSuccess;
 
     char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
@@ -254,6 +260,35 @@ struct Lbc {
         }
     }
 
+    // The panel A[off : off+n, off : off+n] factored on the panel stream as in potrf(), and, one
+    // diagonal block behind it on the solve stream, the rows below the panel solved block column by
+    // block column (right-looking: the product with the block columns already solved, then the
+    // substitution against the diagonal block just factored).  When the panel's last diagonal block
+    // is done only one block column of the solve is left, instead of the whole solve.  The rows below
+    // must be up to date when `rows_ready` has happened.
+    void potrf_and_solve_below(int64_t off, int64_t n, int64_t below, LookAhead* la, hipEvent_t rows_ready,
+                               hipStream_t solve)
+    {
+        const bool f32 = dtype == TBS_F32;
+        const int64_t B = block_for(n), row0 = off + n;
+        note(hipStreamWaitEvent(solve, rows_ready, 0));
+        int piece = 0;
+        for (int64_t p0 = 0; p0 < n; p0 += B, ++piece) {
+            const int64_t nb = (B < n - p0) ? B : n - p0;
+            potrf(off + p0, nb, la->panel);
+            note(hipEventRecord(la->block_done[piece], la->panel));
+            note(hipStreamWaitEvent(solve, la->block_done[piece], 0));
+            if (p0 > 0)
+                note(tbs::launch_gemm_nt(f32, below, nb, p0, -1.0, at(row0, off), lda, at(off + p0, off), lda, 1.0,
+                                         at(row0, off + p0), lda, compute_units(), solve));
+            trsm(row0, below, off + p0, nb, solve);
+            const int64_t rest = n - p0 - nb, r1 = off + p0 + nb;
+            if (rest <= 0) continue;
+            trsm(r1, rest, off + p0, nb, la->panel);
+            note(syrk_impl(false, dtype, rest, nb, -1.0, at(r1, off + p0), lda, 1.0, at(r1, r1), lda, la->panel));
+        }
+    }
+
     // Algorithm 5 at the top level with look-ahead.  The trailing update of panel p is split in three:
     // the diagonal block of the next panel (SYRK), the rows below it (a product), the rest.  The next
     // panel's factorisation (a long chain of small kernels) runs on a second stream: the diagonal
@@ -288,20 +323,32 @@ struct Lbc {
             // by the previous trailing update) and factored
             note(hipStreamWaitEvent(la->panel, la->rest_done, 0));
             note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, la->panel));
-            potrf(r0, nbn, la->panel);
+            // narrow panels (their chain of small kernels paces the factorisation): the solve of the
+            // rows below follows the panel block by block on a third stream
+            const bool piecewise = piecewise_solve && below > 0 && nbn <= 512 &&
+                                   (nbn + block_for(nbn) - 1) / block_for(nbn) <= kSolvePieces;
+            // (Order of the calls: streams may share a hardware queue, in which packets keep the order
+            // of the calls; the panel's launches come first because they pace the last panels.)
+            if (!piecewise) potrf(r0, nbn, la->panel);
             // caller's stream, meanwhile: the rows below that block, then the rest of the update
             if (below > 0)
                 note(tbs::launch_gemm_nt(f32, below, nbn, nb, -1.0, at(r0 + nbn, c0), lda, at(r0, c0), lda, 1.0,
                                          at(r0 + nbn, r0), lda, compute_units(), stream));
             note(hipEventRecord(la->column_ready, stream));
+            if (piecewise) potrf_and_solve_below(r0, nbn, below, la, la->column_ready, la->solve);
             if (below > 0)
                 note(syrk_impl(false, dtype, below, nb, -1.0, at(r0 + nbn, c0), lda, 1.0, at(r0 + nbn, r0 + nbn),
                                lda, stream, reserve_units));
             note(hipEventRecord(la->rest_done, stream));
-            // panel stream: the solve of the rows below needs them up to date
-            note(hipStreamWaitEvent(la->panel, la->column_ready, 0));
-            if (below > 0) trsm(r0 + nbn, below, r0, nbn, la->panel);
-            note(hipEventRecord(la->panel_done, la->panel));
+            if (piecewise) {
+                note(hipEventRecord(la->panel_done, la->solve));
+                note(hipStreamWaitEvent(la->panel, la->panel_done, 0));   // the next diagonal block needs these rows
+            } else {
+                // panel stream: the solve of the rows below needs them up to date
+                note(hipStreamWaitEvent(la->panel, la->column_ready, 0));
+                if (below > 0) trsm(r0 + nbn, below, r0, nbn, la->panel);
+                note(hipEventRecord(la->panel_done, la->panel));
+            }
             note(hipStreamWaitEvent(stream, la->panel_done, 0));
             c0 = r0;
             nb = nbn;
@@ -478,6 +525,7 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
         const long v = std::atol(e);
         if (v > 0) ctx.wide_rows = v;
     }
+    if (const char* e = std::getenv("TBS_POTRF_PIECEWISE")) ctx.piecewise_solve = e[0] != '0';
     if (const char* e = std::getenv("TBS_POTRF_FUSED_ROWS")) {
         const long v = std::atol(e);
         if (v >= 0) ctx.fused_trsm_rows = v;
