@@ -201,7 +201,8 @@ struct Lbc {
     // better use of the few compute units the panel stream has next to a long trailing update.
     int64_t fused_trsm_rows = 6144;
     int64_t wide_rows = 8192;   // trailing matrices at least this tall get double-width panels
-    bool piecewise_solve = true;   // narrow panels: solve of the rows below block by block on a third stream
+    bool piecewise_solve = true;   // solve of the rows below block by block on a third stream
+    int64_t piecewise_width = 1024; // ... for panels up to this width (at most kSolvePieces diagonal blocks)
     hipError_t err = hipSuccess;
 
     char* at(int64_t i, int64_t j) const { return A + ((size_t)i * (size_t)lda + (size_t)j) * es; }
@@ -323,9 +324,10 @@ struct Lbc {
             // by the previous trailing update) and factored
             note(hipStreamWaitEvent(la->panel, la->rest_done, 0));
             note(syrk_impl(false, dtype, nbn, nb, -1.0, at(r0, c0), lda, 1.0, at(r0, r0), lda, la->panel));
-            // narrow panels (their chain of small kernels paces the factorisation): the solve of the
-            // rows below follows the panel block by block on a third stream
-            const bool piecewise = piecewise_solve && below > 0 && nbn <= 512 &&
+            // the solve of the rows below follows the panel block by block on a third stream (for the
+            // last panels the chain of small kernels paces the factorisation; for the first ones the
+            // solve gets an earlier start on the few units it has)
+            const bool piecewise = piecewise_solve && below > 0 && nbn <= piecewise_width &&
                                    (nbn + block_for(nbn) - 1) / block_for(nbn) <= kSolvePieces;
             // (Order of the calls: streams may share a hardware queue, in which packets keep the order
             // of the calls; the panel's launches come first because they pace the last panels.)
@@ -525,7 +527,11 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
         const long v = std::atol(e);
         if (v > 0) ctx.wide_rows = v;
     }
-    if (const char* e = std::getenv("TBS_POTRF_PIECEWISE")) ctx.piecewise_solve = e[0] != '0';
+    if (const char* e = std::getenv("TBS_POTRF_PIECEWISE")) {
+        ctx.piecewise_solve = e[0] != '0';
+        const long v = std::atol(e);
+        if (v >= 64) ctx.piecewise_width = v;
+    }
     if (const char* e = std::getenv("TBS_POTRF_FUSED_ROWS")) {
         const long v = std::atol(e);
         if (v >= 0) ctx.fused_trsm_rows = v;
