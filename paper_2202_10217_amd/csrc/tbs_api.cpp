@@ -276,13 +276,23 @@ struct Lbc {
         int piece = 0;
         for (int64_t p0 = 0; p0 < n; p0 += B, ++piece) {
             const int64_t nb = (B < n - p0) ? B : n - p0;
+            const bool last = p0 + nb >= n;
             potrf(off + p0, nb, la->panel);
-            note(hipEventRecord(la->block_done[piece], la->panel));
-            note(hipStreamWaitEvent(solve, la->block_done[piece], 0));
+            // the last block column of the solve stays on the panel stream (it is what the next step
+            // waits for, and a hand-over between streams costs about 12 us)
+            hipStream_t st = solve;
+            if (!last) {
+                note(hipEventRecord(la->block_done[piece], la->panel));
+                note(hipStreamWaitEvent(solve, la->block_done[piece], 0));
+            } else {
+                note(hipEventRecord(la->block_done[piece], solve));
+                note(hipStreamWaitEvent(la->panel, la->block_done[piece], 0));
+                st = la->panel;
+            }
             if (p0 > 0)
                 note(tbs::launch_gemm_nt(f32, below, nb, p0, -1.0, at(row0, off), lda, at(off + p0, off), lda, 1.0,
-                                         at(row0, off + p0), lda, compute_units(), solve));
-            trsm(row0, below, off + p0, nb, solve);
+                                         at(row0, off + p0), lda, compute_units(), st));
+            trsm(row0, below, off + p0, nb, st);
             const int64_t rest = n - p0 - nb, r1 = off + p0 + nb;
             if (rest <= 0) continue;
             trsm(r1, rest, off + p0, nb, la->panel);
@@ -342,15 +352,12 @@ struct Lbc {
                 note(syrk_impl(false, dtype, below, nb, -1.0, at(r0 + nbn, c0), lda, 1.0, at(r0 + nbn, r0 + nbn),
                                lda, stream, reserve_units));
             note(hipEventRecord(la->rest_done, stream));
-            if (piecewise) {
-                note(hipEventRecord(la->panel_done, la->solve));
-                note(hipStreamWaitEvent(la->panel, la->panel_done, 0));   // the next diagonal block needs these rows
-            } else {
+            if (!piecewise) {
                 // panel stream: the solve of the rows below needs them up to date
                 note(hipStreamWaitEvent(la->panel, la->column_ready, 0));
                 if (below > 0) trsm(r0 + nbn, below, r0, nbn, la->panel);
-                note(hipEventRecord(la->panel_done, la->panel));
             }
+            note(hipEventRecord(la->panel_done, la->panel));
             note(hipStreamWaitEvent(stream, la->panel_done, 0));
             c0 = r0;
             nb = nbn;
