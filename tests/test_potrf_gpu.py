@@ -149,3 +149,29 @@ def test_config4_n16384_probe_residual(tb):
     L = np.tril(d.cpu().numpy())
     del d
     _probe_check(L, S0)
+
+
+def test_calls_on_two_streams_without_waiting_in_between(tb):
+    # two factorisations enqueued back to back on different streams of the caller (no synchronisation
+    # between the calls, info not requested): the library's own streams and events are shared by all calls
+    # on a device, so this pins their ordering; exact integer factors, so any mix-up shows
+    sizes = (3300, 2700)
+    rng = np.random.default_rng(23)
+    Gs, ds, streams = [], [], [torch.cuda.Stream(), torch.cuda.Stream()]
+    for N in sizes:
+        G = np.tril(rng.integers(-1, 2, size=(N, N))).astype(np.float64)
+        np.fill_diagonal(G, rng.integers(1, 3, size=N))
+        Gs.append(G)
+        ds.append(torch.from_numpy(G @ G.T).cuda())
+    ws = [torch.empty(4096, dtype=torch.uint8, device="cuda") for _ in sizes]
+    torch.cuda.synchronize()
+    for rep in range(2):                                     # second round: factor the factors' products again
+        for d, w, s in zip(ds, ws, streams):
+            assert tb.tbs_potrf_lower(d, workspace=w, stream=s, want_info=False) == 0
+        torch.cuda.synchronize()
+        for d, G in zip(ds, Gs):
+            assert np.array_equal(np.tril(d.cpu().numpy()), G)
+        if rep == 0:
+            for d, G in zip(ds, Gs):
+                d.copy_(torch.from_numpy(G @ G.T).cuda())
+            torch.cuda.synchronize()
