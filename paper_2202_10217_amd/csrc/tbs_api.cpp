@@ -55,13 +55,16 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
     auto it = cache.find(key);
     if (it == cache.end()) {
         const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
-        // (TBS_PLAN_COSTS="block_us,slice_us" overrides the two fixed costs, for measurements)
-        double block_us = 20.0, slice_us = 0.03 * tile_us;
+        // fixed costs: a block (prologue, epilogue, taking it from the list), a part of a cut block, and
+        // per part of the block again for summing them (TBS_PLAN_COSTS="block_us,part_us,per_part_us"
+        // overrides them, for measurements)
+        double block_us = 20.0, slice_us = 0.03 * tile_us, per_part_us = 0.0;
         if (const char* c = std::getenv("TBS_PLAN_COSTS")) {
-            double b = 0.0, sl = 0.0;
-            if (std::sscanf(c, "%lf,%lf", &b, &sl) == 2 && b >= 0.0 && sl >= 0.0) {
+            double b = 0.0, sl = 0.0, pp = 0.0;
+            if (std::sscanf(c, "%lf,%lf,%lf", &b, &sl, &pp) >= 2 && b >= 0.0 && sl >= 0.0 && pp >= 0.0) {
                 block_us = b;
                 slice_us = sl;
+                per_part_us = pp;
             }
         }
         const double overhead_tiles = block_us / tile_us;
@@ -93,7 +96,7 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
                 if (tbs::apply_slicing(p, tbs::Slicing{st, sr, tb, ts}, &q)) p = q;
             }
         } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family, max_slices,
-                                     slice_us / tile_us)) {
+                                     slice_us / tile_us, per_part_us / tile_us)) {
             return nullptr;
         }
         it = cache.emplace(key, p).first;

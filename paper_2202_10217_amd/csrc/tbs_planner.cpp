@@ -194,7 +194,8 @@ bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
     return true;
 }
 
-double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles)
+double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles,
+                         double slice_per_part_tiles)
 {
     std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
     for (int32_t u = 0; u < ncu; ++u) free_at.push(0.0);
@@ -217,7 +218,9 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, doub
         } else {
             continue;                                       // empty block: exits at once
         }
-        if (it.slices > 1) tiles = tiles / it.slices + slice_overhead_tiles;   // plus storing / summing the parts
+        // a part also stores its accumulators, and the last one to finish sums all parts: that cost
+        // grows with their number and is what the block's completion waits for
+        if (it.slices > 1) tiles = tiles / it.slices + slice_overhead_tiles + slice_per_part_tiles * it.slices;
         const double start = free_at.top();
         free_at.pop();
         const double stop = start + tiles + overhead_tiles;
@@ -228,19 +231,19 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, doub
 }
 
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family,
-                 int32_t max_slices, double slice_overhead_tiles)
+                 int32_t max_slices, double slice_overhead_tiles, double slice_per_part_tiles)
 {
     if (square) {
         // rectangles only; for small matrices the block shape with the shortest simulated makespan
         // (the same rule as below, so that the baseline is not handicapped by coarse blocks)
         if (!build_plan(T, PlanTuning{0, kRectRows, kRectCols, false}, out)) return false;
         if (0.5 * (double)T * (double)T / (double)std::max(ncu, 1) > 200.0 || T < 2) return true;
-        double best_sq = simulate_makespan(*out, ncu, overhead_tiles, slice_overhead_tiles);
+        double best_sq = simulate_makespan(*out, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);
         const int32_t sq_shapes[4][2] = {{2, 2}, {1, 3}, {1, 2}, {1, 1}};
         for (const auto& sh : sq_shapes) {
             Plan cand;
             if (!build_plan(T, PlanTuning{0, sh[0], sh[1], false}, &cand)) continue;
-            const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles);
+            const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);
             if (span < best_sq * 0.98) {
                 best_sq = span;
                 *out = cand;
@@ -254,7 +257,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     // with many blocks per compute unit the granularity of the tail does not matter
     const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
     if (per_unit > 200.0 || T < 2) return true;
-    double best = simulate_makespan(*out, ncu, overhead_tiles, slice_overhead_tiles);
+    double best = simulate_makespan(*out, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);
     // cutting blocks along the contraction dimension costs a workspace and an extra pass over the
     // parts: only for problems with few tiles per compute unit, and only for a clear gain
     const bool slicing = max_slices > 1 && per_unit <= 40.0;
@@ -262,24 +265,33 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     Plan sliced = *out;
     bool have_sliced = false;
     auto try_slicings = [&](const Plan& base) {
+        // all blocks of a kind cut alike (tri, rect), or only the end of the list cut (that many items,
+        // that finely): the end decides when the last unit finishes
         const int32_t whole[3] = {1, 2, 4};
-        const int32_t tails[5][2] = {{0, 1}, {16, 16}, {32, 8}, {64, 4}, {128, 4}};
+        const int32_t tail_items[9] = {16, 24, 32, 36, 40, 48, 64, 96, 128};
+        const int32_t tail_parts[6] = {3, 4, 5, 6, 8, 16};
+        auto consider = [&](const Slicing& sl) {
+            Plan q;
+            if (!apply_slicing(base, sl, &q)) return;
+            // at most 128 MB of workspace (6 tiles of doubles per part)
+            if ((int64_t)q.n_ws_blocks * q.ws_slices * 6 * kTile * kTile * 8 > ((int64_t)128 << 20)) return;
+            const double span = simulate_makespan(q, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);
+            if (span < best_sliced * 0.995) {
+                best_sliced = span;
+                sliced = q;
+                have_sliced = true;
+            }
+        };
         for (int32_t st : whole)
-            for (int32_t sr : whole)
-                for (const auto& tl : tails) {
-                    if (st == 1 && sr == 1 && tl[0] == 0) continue;
-                    if (st > max_slices || sr > max_slices || tl[1] > max_slices) continue;
-                    Plan q;
-                    if (!apply_slicing(base, Slicing{st, sr, tl[0], tl[1]}, &q)) continue;
-                    // at most 128 MB of workspace (6 tiles of doubles per part)
-                    if ((int64_t)q.n_ws_blocks * q.ws_slices * 6 * kTile * kTile * 8 > ((int64_t)128 << 20)) continue;
-                    const double span = simulate_makespan(q, ncu, overhead_tiles, slice_overhead_tiles);
-                    if (span < best_sliced * 0.995) {
-                        best_sliced = span;
-                        sliced = q;
-                        have_sliced = true;
-                    }
-                }
+            for (int32_t sr : whole) {
+                if (st > max_slices || sr > max_slices) continue;
+                if (st > 1 || sr > 1) consider(Slicing{st, sr, 0, 1});
+                for (int32_t tp : {4, 8, 16})
+                    if (tp <= max_slices && tp > std::max(st, sr)) consider(Slicing{st, sr, 64, tp});
+            }
+        for (int32_t ti : tail_items)
+            for (int32_t tp : tail_parts)
+                if (tp <= max_slices) consider(Slicing{1, 1, ti, tp});
     };
     if (slicing) try_slicings(*out);
     const int32_t shapes[5][2] = {{2, 3}, {2, 2}, {1, 3}, {1, 2}, {1, 1}};
@@ -291,7 +303,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
                     tune.xor_family = xor_family;
                     Plan cand;
                     if (!build_plan(T, tune, &cand)) continue;
-                    const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles);
+                    const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);
                     if (span < best * 0.98) {               // prefer the coarser plan on near ties
                         best = span;
                         *out = cand;

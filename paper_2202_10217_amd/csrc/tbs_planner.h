@@ -44,12 +44,14 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
 // and the one with the shortest simulated makespan on `ncu` compute units is taken (blocks are
 // dispatched in list order to the first free unit; a block costs its tiles plus `overhead_tiles`).
 // max_slices > 1 lets the choice cut blocks along the contraction dimension (at most that finely);
-// a part of a cut block costs `slice_overhead_tiles` on top (storing, later summing the parts).
+// a part of a block cut into S parts costs `slice_overhead_tiles + S * slice_per_part_tiles` on top
+// (storing the part; the last part to finish sums all of them).
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family = true,
-                 int32_t max_slices = 1, double slice_overhead_tiles = 0.03);
+                 int32_t max_slices = 1, double slice_overhead_tiles = 0.03, double slice_per_part_tiles = 0.0);
 
 // Makespan, in tile units, of dispatching the plan's blocks in order onto ncu units.
-double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles = 0.03);
+double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles = 0.03,
+                         double slice_per_part_tiles = 0.0);
 
 struct PlanStats {
     int32_t levels;
