@@ -140,6 +140,10 @@ tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32
  *   returns and stores 0, or the 1-based index of the first pivot that is not > 0 (the return
  *   value is then TBS_ENOTSPD and the contents of A are unspecified).  With NULL the call is
  *   asynchronous and a failed pivot goes unreported.
+ *   Large matrices are factored with look-ahead on two more streams that the library creates per
+ *   device on first use (default priority) and keeps; their work is ordered before and after the
+ *   caller's stream by events, so the caller sees an ordinary stream-ordered call.  Calls from
+ *   several host threads on one device are enqueued one after the other.
  * ---------------------------------------------------------------------------------------------- */
 tbs_status tbs_potrf_lower_workspace(tbs_dtype dtype, int64_t N, size_t* bytes);
 
