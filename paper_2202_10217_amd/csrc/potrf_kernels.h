@@ -12,9 +12,10 @@ hipError_t launch_potrf_tile(bool f32, int nb, void* A, int64_t lda, int32_t* in
                              hipStream_t stream);
 
 // The same for a diagonal block of n <= 128 columns, in one workgroup (factor the first tile, solve and
-// update the second, factor it).  Returns hipErrorInvalidValue for n > 128.
+// update the second, factor it).  Returns hipErrorInvalidValue for n > 128.  `done` (optional): an event
+// that happens when the block is factored.
 hipError_t launch_potrf_block(bool f32, int n, void* A, int64_t lda, int32_t* info, int32_t index0,
-                              hipStream_t stream);
+                              hipStream_t stream, hipEvent_t done = nullptr);
 
 // X (m x nb, nb <= 64) <- X * L^{-T} by forward substitution, L the lower triangular nb x nb tile at
 // `L` (leading dimension ldl); X in place.  The column-scaling and update steps of Algorithm 2 for

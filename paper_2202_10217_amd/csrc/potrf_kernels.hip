@@ -2,6 +2,7 @@
 // (the paper's Algorithm 5 calls a one-tile Cholesky for A[I0, I0]; at the bottom of the
 // recursion that is Algorithm 2 on a tile held in LDS).
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "potrf_kernels.h"
@@ -627,16 +628,22 @@ hipError_t launch_trsm_tile(bool f32, int64_t m, int nb, const void* L, int64_t 
 }
 
 hipError_t launch_potrf_block(bool f32, int n, void* A, int64_t lda, int32_t* info, int32_t index0,
-                              hipStream_t stream)
+                              hipStream_t stream, hipEvent_t done)
 {
-    if (n <= kPT) return launch_potrf_tile(f32, n, A, lda, info, index0, stream);
     if (n > 2 * kPT) return hipErrorInvalidValue;
+    if (n <= kPT) {
+        const hipError_t e = launch_potrf_tile(f32, n, A, lda, info, index0, stream);
+        if (e != hipSuccess || !done) return e;
+        return hipEventRecord(done, stream);
+    }
+    // `done`: the kernel's own completion is the event (no separate packet in the queue between this
+    // kernel and the next one of the stream)
     if (f32)
-        hipLaunchKernelGGL(potrf_block_kernel<float>, dim3(1), dim3(256), 0, stream, n, (float*)A, lda, info,
-                           index0);
+        hipExtLaunchKernelGGL(potrf_block_kernel<float>, dim3(1), dim3(256), 0, stream, nullptr, done, 0, n,
+                              (float*)A, lda, info, index0);
     else
-        hipLaunchKernelGGL(potrf_block_kernel<double>, dim3(1), dim3(256), 0, stream, n, (double*)A, lda, info,
-                           index0);
+        hipExtLaunchKernelGGL(potrf_block_kernel<double>, dim3(1), dim3(256), 0, stream, nullptr, done, 0, n,
+                              (double*)A, lda, info, index0);
     return hipGetLastError();
 }
 

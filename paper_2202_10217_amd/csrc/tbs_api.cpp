@@ -280,14 +280,20 @@ struct Lbc {
         for (int64_t p0 = 0; p0 < n; p0 += B, ++piece) {
             const int64_t nb = (B < n - p0) ? B : n - p0;
             const bool last = p0 + nb >= n;
-            potrf(off + p0, nb, la->panel);
             // the last block column of the solve stays on the panel stream (it is what the next step
             // waits for, and a hand-over between streams costs about 12 us)
             hipStream_t st = solve;
             if (!last) {
-                note(hipEventRecord(la->block_done[piece], la->panel));
+                if (nb <= 2 * kTile) {                                  // the kernel's completion is the event
+                    note(tbs::launch_potrf_block(f32, (int)nb, at(off + p0, off + p0), lda, info,
+                                                 (int32_t)(off + p0), la->panel, la->block_done[piece]));
+                } else {
+                    potrf(off + p0, nb, la->panel);
+                    note(hipEventRecord(la->block_done[piece], la->panel));
+                }
                 note(hipStreamWaitEvent(solve, la->block_done[piece], 0));
             } else {
+                potrf(off + p0, nb, la->panel);
                 note(hipEventRecord(la->block_done[piece], solve));
                 note(hipStreamWaitEvent(la->panel, la->block_done[piece], 0));
                 st = la->panel;
