@@ -331,8 +331,17 @@ struct Lbc {
         // the shadow of that update
         auto width_for = [&](int64_t rest) { return (rest >= wide_rows) ? 2 * B : B; };
         int64_t nb = width_for(N);                                      // width of panel p
-        potrf(0, nb, stream);
-        trsm(nb, N - nb, 0, nb, stream);
+        if (piecewise_solve && nb <= piecewise_width && (nb + block_for(nb) - 1) / block_for(nb) <= kSolvePieces) {
+            // the first panel: factorisation and, block by block behind it, the solve of all other rows
+            note(hipEventRecord(la->column_ready, stream));             // the caller's earlier work
+            note(hipStreamWaitEvent(la->panel, la->column_ready, 0));
+            potrf_and_solve_below(0, nb, N - nb, la, la->column_ready, la->solve);
+            note(hipEventRecord(la->panel_done, la->panel));
+            note(hipStreamWaitEvent(stream, la->panel_done, 0));
+        } else {
+            potrf(0, nb, stream);
+            trsm(nb, N - nb, 0, nb, stream);
+        }
         note(hipEventRecord(la->rest_done, stream));
         for (int64_t c0 = 0; c0 + nb < N;) {                            // c0: first column of panel p
             const int64_t r0 = c0 + nb, rest = N - r0;                  // trailing matrix starts at r0
