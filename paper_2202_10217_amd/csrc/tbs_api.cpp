@@ -311,11 +311,12 @@ struct Lbc {
 
     // Algorithm 5 at the top level with look-ahead.  The trailing update of panel p is split in three:
     // the diagonal block of the next panel (SYRK), the rows below it (a product), the rest.  The next
-    // panel's factorisation (a long chain of small kernels) runs on a second stream: the diagonal
+    // panel's factorisation (a long chain of small kernels) runs on the panel stream: the diagonal
     // block is updated there and factored while the caller's stream computes the product and then the
     // rest of the update (which leaves a few compute units free); the solve of the rows below follows
-    // on the second stream once the product is done.  The streams touch disjoint parts of A: diagonal
-    // block / rows below it / columns right of the next panel; all read the columns of panel p.
+    // the factorisation block by block on the solve stream (potrf_and_solve_below), or as a whole on the
+    // panel stream.  The streams touch disjoint parts of A: diagonal block / rows below it / columns
+    // right of the next panel; all read the columns of panel p.
     void potrf_top(int64_t N)
     {
         const int64_t B = block_for(N);
