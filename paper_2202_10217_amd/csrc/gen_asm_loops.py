@@ -33,8 +33,9 @@ reads, waits, scalar instructions and the barrier are free).  Hence:
   - one iteration of the loop is one pass over the whole ring, so the position of a buffer is a
     constant: operand reads carry it in their offset field (16 bits; one set of address registers
     per 64 KB of the ring, set up once), the LDS target of a load is a constant added to M0;
-  - the lanes' global offsets never change; the scalar unit moves the two matrix pointers one chunk
-    on after each request (copies in fixed scalar registers, declared clobbered);
+  - the lanes' global offsets never change (they address a row inside a panel, so 32 bits suffice for
+    matrices of any size); the scalar unit moves one pointer per panel one chunk on after each request
+    (fixed scalar registers, declared clobbered);
   - rarely executed code (the waits near the end, the last k-step without a request) sits after the
     loop, so the steady state takes no branch except the back edge once per pass.
 
@@ -68,9 +69,7 @@ TYPES = {
 }
 
 TMP_BASE = 128                   # first vector register the loop uses as scratch (declared clobbered)
-GR_N = 92                        # scalar registers s[92:93], s[94:95]: the moving row-side / column-side pointers
-GQ_N = 94
-GR, GQ = f"s[{GR_N}:{GR_N + 1}]", f"s[{GQ_N}:{GQ_N + 1}]"
+PB = 86                          # scalar registers s[86:95]: the moving pointers of up to five panels
 
 
 def vreg(first, n):
@@ -106,8 +105,7 @@ def gen(ty, shape_name, slots_mask):
     RING = NBUF * CB
     NSEG = (RING + 65535) // 65536                          # 64 KB segments an offset field can span
     LPC = 2 * npu                                           # loads per wavefront and chunk
-    uses_q = any(S["col_side"](p) for p in panels)
-    uses_r = any(not S["col_side"](p) for p in panels)
+    pair = {p: f"s[{PB + 2 * n}:{PB + 2 * n + 1}]" for n, p in enumerate(panels)}   # pointer of panel p
     pieces = [("a", i, rb) for i in a_used for rb in range(4)] + [("b", j) for j in b_used]
     n_op, opr = len(pieces), T["opregs"]
     set_base = [TMP_BASE, TMP_BASE + n_op * opr]
@@ -141,21 +139,19 @@ def gen(ty, shape_name, slots_mask):
         return out
 
     def issue(buf):
-        """Request the next chunk into ring buffer buf and move the matrix pointers one chunk on."""
+        """Request the next chunk into ring buffer buf and move the panel pointers one chunk on."""
         out = []
         for q in range(LPC):
             p, h = panels[q // 2], q % 2
-            base = GQ if S["col_side"](p) else GR
             out += [f"s_add_u32 m0, %[m0b], {buf * CB + sp[p] * PANEL_BYTES + h * HALF_BYTES}", "s_nop 0",
-                    f"global_load_lds_dwordx4 %[go{q}], {base}"]
-        for used, base in ((uses_r, GR_N), (uses_q, GQ_N)):
-            if used:
-                out += [f"s_add_u32 s{base}, s{base}, %[step]", f"s_addc_u32 s{base + 1}, s{base + 1}, 0"]
+                    f"global_load_lds_dwordx4 %[go{q}], {pair[p]}"]
+        for n in range(npu):
+            out += [f"s_add_u32 s{PB + 2 * n}, s{PB + 2 * n}, %[step]", f"s_addc_u32 s{PB + 2 * n + 1}, s{PB + 2 * n + 1}, 0"]
         return out
 
     L = []
     # ---- prologue: request the first min(NBUF, nch) chunks, wait for chunk 0 --------------------
-    L += [f"s_mov_b64 {GR}, %[gR]", f"s_mov_b64 {GQ}, %[gQ]", "s_mov_b32 %[cnt], 0"]
+    L += [f"s_mov_b64 {pair[p]}, %[gp{n}]" for n, p in enumerate(panels)] + ["s_mov_b32 %[cnt], 0"]
     for n in range(NBUF):
         # (a scalar register written by the scalar unit may be read by a memory instruction 5 wait
         # states later at the earliest: the moved pointers, also after the s_mov_b64 above)
@@ -201,7 +197,8 @@ def gen(ty, shape_name, slots_mask):
     accs = ", ".join(f'[c{n}_{rb}] "+a"(acc[{n}][{rb}])' for n, _ in slots for rb in range(4))
     gos = ", ".join(f'[go{q}] "v"(go[{q}])' for q in range(LPC))
     ads = ", ".join(f'[ada{j}] "v"(g.ada[{j}]), [adb{j}] "v"(g.adb[{j}])' for j in range(KS))
-    clob = ", ".join([f'"v{r}"' for r in range(TMP_BASE, last_tmp + 1)] + [f'"s{r}"' for r in range(GR_N, GR_N + 4)])
+    gps = ", ".join(f'[gp{n}] "s"(g.gP[{n}])' for n in range(npu))
+    clob = ", ".join([f'"v{r}"' for r in range(TMP_BASE, last_tmp + 1)] + [f'"s{r}"' for r in range(PB, PB + 2 * npu)])
     name = f"asm_loop_{ty}_{shape_name}_{slots_mask:02x}"
     fn = f"""
 // {ty}, {shape_name} block, slots 0x{slots_mask:02x}: panels {panels}, ring of {NBUF} chunk buffers of {CB} bytes,
@@ -215,7 +212,8 @@ __device__ __forceinline__ void {name}(Cfg<{ty}>::acc_t (&acc)[6][4], const AsmL
           [cnt] "=&s"(cnt), [tmp] "=&s"(tmp)
         : {gos},
           {ads},
-          [gR] "s"(g.gR), [gQ] "s"(g.gQ), [nch] "s"(g.nch), [step] "s"(g.step), [m0b] "s"(g.m0base)
+          {gps},
+          [nch] "s"(g.nch), [step] "s"(g.step), [m0b] "s"(g.m0base)
         : "memory", "scc", {clob});
 }}
 """

@@ -270,8 +270,7 @@ extern "C" int tbs_phase_fetch(unsigned long long* host, int reset)
 struct AsmLoopArgs {
     uint32_t ada[8];        // LDS byte address of the lane's row-side operand piece for k-step j
     uint32_t adb[8];        // same for the column side (includes the wavefront's 16-row group)
-    const void* gR;         // row-side matrix
-    const void* gQ;         // column-side matrix
+    const void* gP[5];      // first element of each panel the block uses (tile row, first column), in panel order
     uint32_t nch;           // chunks, >= 1
     uint32_t step;          // bytes per chunk along a row
     uint32_t m0base;        // LDS byte address of the wavefront's 1 KB slice in panel 0, half 0, buffer 0
@@ -384,8 +383,8 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     if constexpr (FAST) {
         // Addresses for the assembly loop (layout and schedule: gen_asm_loops.py).  In LDS a chunk
         // buffer holds the used panels back to back, 64 rows of 128 bytes each, the 16-byte pieces of
-        // row r permuted by XOR with r mod 8.  The caller has checked that the matrices are smaller
-        // than 4 GiB: global offsets are 32-bit.
+        // row r permuted by XOR with r mod 8.  Global addresses are a 64-bit pointer per panel plus a
+        // 32-bit offset per lane; the caller has checked that 64 rows of either matrix span less than 4 GiB.
         constexpr int ES = (int)sizeof(T);
         typedef __attribute__((address_space(3))) unsigned char lds_byte;
         const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte*)lds;
@@ -403,21 +402,22 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                 g.adb[j] = lds0 + a + (uint32_t)w * 2048;
             }
         }
-        g.gR = m.R;
-        g.gQ = m.Q;
         g.nch = (uint32_t)nchunks;
         g.step = (uint32_t)(KC * ES);
         g.m0base = lds0 + (uint32_t)w * 1024;
         uint32_t go[10];
-        int q = 0;
+        int q = 0, np_used = 0;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             if (!((PANELS >> p) & 1u)) continue;
+            g.gP[np_used++] = base[p] + (int64_t)prow[p] * kTile * ld[p];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 // this lane's piece of the wavefront's 8 rows: row 8w + lane/8 of the half-panel,
-                // global piece (lane%8) ^ (lane/8) so that it lands at LDS position lane%8
-                const int64_t row = (int64_t)prow[p] * kTile + h * 32 + w * 8 + (lane >> 3);
+                // global piece (lane%8) ^ (lane/8) so that it lands at LDS position lane%8; the offset is
+                // relative to the panel's first row (64 rows of a matrix stay below 4 GiB: checked by
+                // the caller)
+                const int64_t row = h * 32 + w * 8 + (lane >> 3);
                 go[q++] = (uint32_t)(row * ld[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
             }
         }
@@ -629,10 +629,11 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
             }
         }
     constexpr int KC = Cfg<T>::KC;
-    const int64_t lim = (int64_t)1 << 32;                   // the assembly loop uses 32-bit byte offsets
+    // the assembly loop addresses a panel's 64 rows with 32-bit byte offsets from the panel's start
+    const int64_t lim = (int64_t)1 << 32;
     const bool fast_ok = m.M >= KC && m.M % KC == 0 && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
-                         (int64_t)m.nr * m.ldr * (int64_t)sizeof(T) < lim &&
-                         (int64_t)m.nq * m.ldq * (int64_t)sizeof(T) < lim;
+                         (int64_t)kTile * m.ldr * (int64_t)sizeof(T) < lim &&
+                         (int64_t)kTile * m.ldq * (int64_t)sizeof(T) < lim;
     if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
     block_body<T, Shape, (1u << Shape::NSLOT) - 1, false, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
 }

@@ -143,9 +143,9 @@ def test_leading_dimensions_and_unaligned_views(tb, dtype):
 
 
 def test_matrices_of_4_gib_or_more_use_64_bit_offsets(tb):
-    # the assembly loop addresses A with 32-bit byte offsets and is only used below 4 GiB; a matrix whose
-    # rows are spread over 4.6 GB (huge leading dimension, few columns) must take the other path and
-    # give the same bits on integer data
+    # the assembly loop addresses the 64 rows of a panel with 32-bit byte offsets from a 64-bit pointer per
+    # panel; a matrix whose rows are spread over 4.6 GB (huge leading dimension, few columns) must give
+    # the same bits on integer data
     N, M, lda = 4096, 64, 140000
     A = inputs.small_int_matrix(N, M, seed=21)
     C0 = inputs.symmetric_uniform(N, seed=22, int_range=(-3, 3))
