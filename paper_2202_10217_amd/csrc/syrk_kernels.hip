@@ -337,8 +337,9 @@ struct SliceCtx {
 // and the chunk after that is requested from global memory, all hidden behind the last k-step's
 // MFMAs.
 //   FAST: the slots SLOTS are exactly the block's, their panels are whole (64 rows inside the
-//   matrix), 16-byte loads are legal and M is a positive multiple of KC.  The chunk loop then has no
-//   test and no branch, so the accumulators stay in their registers across it.
+//   matrix), 16-byte loads are legal and M >= KC.  The chunk loop over the whole chunks then has no
+//   test and no branch, so the accumulators stay in their registers across it; columns beyond the
+//   last whole chunk go through the checked loop afterwards.
 //   !FAST: anything else (ragged edges, odd leading dimensions, unusual slot sets); same schedule
 //   with every access checked.
 template <typename T, class Shape, uint32_t SLOTS, bool FAST, bool CAN_SLICE>
@@ -402,7 +403,7 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                 g.adb[j] = lds0 + a + (uint32_t)w * 2048;
             }
         }
-        g.nch = (uint32_t)nchunks;
+        g.nch = (uint32_t)(M / KC);                         // whole chunks; the rest follows below
         g.step = (uint32_t)(KC * ES);
         g.m0base = lds0 + (uint32_t)w * 1024;
         uint32_t go[10];
@@ -432,19 +433,23 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
             atomicAdd(&g_phase[2], 1ull);
         }
 #endif
-    } else {
-      if (nchunks > 0) {
+    }
+    // The checked loop over the columns [k_begin, M) (everything, or what the assembly loop left over):
+    // two padded LDS buffers, chunks staged through registers, every access checked.
+    auto checked_columns = [&](int k_begin) {
+        const int nch = (M - k_begin + KC - 1) / KC;
+        if (nch <= 0) return;
         const bool aligned = vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq);
-        st.load_checked(M, 0, aligned && KC <= M, tid);
+        st.load_checked(M, k_begin, aligned && k_begin + KC <= M, tid);
         st.store(lds, tid);
         __syncthreads();
-        if (nchunks > 1) st.load_checked(M, KC, aligned && 2 * KC <= M, tid);
+        if (nch > 1) st.load_checked(M, k_begin + KC, aligned && k_begin + 2 * KC <= M, tid);
         Ops op[2];
         op[0].load(lds, 0, w, lane);
-        for (int ch = 0; ch < nchunks; ++ch) {
+        for (int ch = 0; ch < nch; ++ch) {
             T* cur = lds + (ch & 1) * kBufElems;
             T* nxt = lds + ((ch + 1) & 1) * kBufElems;
-            const bool more = ch + 1 < nchunks;
+            const bool more = ch + 1 < nch;
 #pragma unroll
             for (int ks = 0; ks < KS - 1; ++ks) {
                 op[(ks + 1) & 1].load(cur, ks + 1, w, lane);
@@ -454,14 +459,22 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
             __syncthreads();
             if (more) {
                 op[0].load(nxt, 0, w, lane);
-                if (ch + 2 < nchunks) {
-                    const int k0 = (ch + 2) * KC;
+                if (ch + 2 < nch) {
+                    const int k0 = k_begin + (ch + 2) * KC;
                     st.load_checked(M, k0, aligned && k0 + KC <= M, tid);
                 }
             }
             mfma_step<T, Shape, SLOTS>(op[(KS - 1) & 1], acc, pmask);
         }
-      }
+    };
+    if constexpr (FAST) {
+        // the columns beyond the last whole chunk (M is no multiple of KC)
+        if (M % KC != 0) {
+            __syncthreads();                                // the ring is free: every wavefront has left the loop
+            checked_columns(M - M % KC);
+        }
+    } else {
+        checked_columns(0);
     }
 
     if (CAN_SLICE && sc.part != nullptr) {                  // uniform
@@ -631,7 +644,7 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
     constexpr int KC = Cfg<T>::KC;
     // the assembly loop addresses a panel's 64 rows with 32-bit byte offsets from the panel's start
     const int64_t lim = (int64_t)1 << 32;
-    const bool fast_ok = m.M >= KC && m.M % KC == 0 && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
+    const bool fast_ok = m.M >= KC && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
                          (int64_t)kTile * m.ldr * (int64_t)sizeof(T) < lim &&
                          (int64_t)kTile * m.ldq * (int64_t)sizeof(T) < lim;
     if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
