@@ -10,7 +10,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT_DIR = os.path.join(HERE, "lib")
 OUT = os.path.join(OUT_DIR, "libtbs_syrk.so")
-SOURCES = ["syrk_kernels.hip", "potrf_kernels.hip", "tbs_planner.cpp", "tbs_api.cpp"]
 
 
 def generate_loops() -> str:
@@ -23,22 +22,49 @@ def generate_loops() -> str:
 
 
 def build(verbose: bool = False) -> str:
+    """Compiles the translation units in parallel (the SYRK kernels are compiled once per element type
+    and kernel family: each takes a minute or two) and links them."""
+    from concurrent.futures import ThreadPoolExecutor
     os.makedirs(OUT_DIR, exist_ok=True)
+    obj_dir = os.path.join(OUT_DIR, "obj")
+    os.makedirs(obj_dir, exist_ok=True)
     generate_loops()
-    cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           # no packed fp32 arithmetic: some forms have given wrong results on this hardware
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", OUT] + [os.path.join(CSRC, s) for s in SOURCES]
+    common = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
+              # no packed fp32 arithmetic: some forms have given wrong results on this hardware
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     if verbose:
-        cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
-    res = subprocess.run(cmd, capture_output=True, text=True)
+        common.insert(1, "-Rpass-analysis=kernel-resource-usage")
+    syrk = os.path.join(CSRC, "syrk_kernels.hip")
+    units = [("syrk_f64", syrk, ["-DTBS_UNIT_SYRK", "-DTBS_UNIT_TYPE=double"]),
+             ("syrk_f32", syrk, ["-DTBS_UNIT_SYRK", "-DTBS_UNIT_TYPE=float"]),
+             ("gemm_f64", syrk, ["-DTBS_UNIT_GEMM", "-DTBS_UNIT_TYPE=double"]),
+             ("gemm_f32", syrk, ["-DTBS_UNIT_GEMM", "-DTBS_UNIT_TYPE=float"]),
+             ("syrk_dispatch", syrk, ["-DTBS_UNIT_DISPATCH"]),
+             ("potrf_kernels", os.path.join(CSRC, "potrf_kernels.hip"), []),
+             ("tbs_planner", os.path.join(CSRC, "tbs_planner.cpp"), []),
+             ("tbs_api", os.path.join(CSRC, "tbs_api.cpp"), [])]
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+
+    def compile_unit(unit):
+        name, src, defs = unit
+        obj = os.path.join(obj_dir, name + ".o")
+        res = subprocess.run(common + defs + ["-c", src, "-o", obj], capture_output=True, text=True)
+        err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed on " + name + ":\n" + err)
+        return obj, err
+
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+        results = list(pool.map(compile_unit, units))
+    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + [o for o, _ in results],
+                         capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err:
-        print(err)
+        raise RuntimeError("hipcc failed at the link step:\n" + res.stderr)
+    if verbose:
+        for _, err in results:
+            if err:
+                print(err)
     return OUT
 
 

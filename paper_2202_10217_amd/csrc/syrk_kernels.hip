@@ -336,15 +336,16 @@ struct SliceCtx {
 // the other LDS buffer, the workgroup synchronises, the first operands of the next chunk are read
 // and the chunk after that is requested from global memory, all hidden behind the last k-step's
 // MFMAs.
-//   FAST: the slots SLOTS are exactly the block's, their panels are whole (64 rows inside the
-//   matrix), 16-byte loads are legal and M >= KC.  The chunk loop over the whole chunks then has no
+//   FAST: the slots SLOTS are exactly the block's, 16-byte loads are legal and M >= KC (`ragged`: a
+//   panel has fewer than 64 rows inside the matrix; the loop then reads its last row in place of the
+//   missing ones and the epilogue checks rows and columns).  The chunk loop over the whole chunks then has no
 //   test and no branch, so the accumulators stay in their registers across it; columns beyond the
 //   last whole chunk go through the checked loop afterwards.
 //   !FAST: anything else (ragged edges, odd leading dimensions, unusual slot sets); same schedule
 //   with every access checked.
 template <typename T, class Shape, uint32_t SLOTS, bool FAST, bool CAN_SLICE>
 __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
-                                           uint32_t dmask, T* lds, const SliceCtx<T>& sc)
+                                           uint32_t dmask, T* lds, const SliceCtx<T>& sc, bool ragged)
 {
     constexpr int NP = Shape::NP;
     constexpr int KC = Cfg<T>::KC, KS = KC / 4, LDK = Cfg<T>::LDK;
@@ -418,7 +419,10 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                 // global piece (lane%8) ^ (lane/8) so that it lands at LDS position lane%8; the offset is
                 // relative to the panel's first row (64 rows of a matrix stay below 4 GiB: checked by
                 // the caller)
-                const int64_t row = h * 32 + w * 8 + (lane >> 3);
+                // (a panel that reaches beyond the matrix: its last row stands in for the missing ones;
+                // what is computed from them belongs to rows or columns of C that are never stored)
+                const int rows_in = min(kTile, nrows[p] - prow[p] * kTile);
+                const int64_t row = min(h * 32 + w * 8 + (lane >> 3), rows_in - 1);
                 go[q++] = (uint32_t)(row * ld[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
             }
         }
@@ -526,7 +530,7 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
 
     // Epilogue.
     const int col16 = w * 16 + (lane & 15);
-    if constexpr (FAST) {
+    if (FAST && !ragged) {
         // the old values of three tiles are requested at once (the operand registers of the loop are
         // free now), then their strips are computed and stored
         const bool rd = m.beta != T(0);
@@ -608,8 +612,9 @@ __device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Sha
                     const int nrows = Shape::col_side(p) ? m.nq : m.nr;
                     whole = whole && (prow[p] + 1) * kTile <= nrows;
                 }
-            if (!whole) return false;
-            block_body<T, Shape, SLOTS, true, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
+            // a panel that reaches beyond the matrix (ragged last tile row) keeps the fast loop; the
+            // epilogue then checks every row and column
+            block_body<T, Shape, SLOTS, true, CAN_SLICE>(m, prow, pmask, dmask, lds, sc, !whole);
             return true;
         }
         return try_fast<T, Shape, IDX + 1, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
@@ -648,7 +653,7 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
                          (int64_t)kTile * m.ldr * (int64_t)sizeof(T) < lim &&
                          (int64_t)kTile * m.ldq * (int64_t)sizeof(T) < lim;
     if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
-    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false, CAN_SLICE>(m, prow, pmask, dmask, lds, sc);
+    block_body<T, Shape, (1u << Shape::NSLOT) - 1, false, CAN_SLICE>(m, prow, pmask, dmask, lds, sc, true);
 }
 
 // ---- the kernels: workgroup -> block(s) -> code path ------------------------------------------
@@ -775,11 +780,11 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
 // Counter pairs for persistent launches, zero at load time and zero again after every launch.
 // Launches that may run at the same time must use different pairs: they are handed out round robin.
 constexpr int kCounterPairs = 64;
-__device__ unsigned int g_syrk_counters[kCounterPairs][2];
+static __device__ unsigned int g_syrk_counters[kCounterPairs][2];
 // Counters of the sliced blocks of a launch (parts finished), one set per launch in flight, handed
 // out like the pairs above; zero at load time, set back to zero by the workgroup that sums a block.
 constexpr int kSliceCounters = 512;
-__device__ unsigned int g_slice_counters[kCounterPairs][kSliceCounters];
+static __device__ unsigned int g_slice_counters[kCounterPairs][kSliceCounters];
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, rectangular blocks of mr x nc tiles
 // (mr <= 2, nc <= 3), one workgroup per block.
@@ -812,7 +817,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
 }
 
 template <typename T>
-static hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
+hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
                                 int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* ws,
                                 hipStream_t stream)
 {
@@ -859,25 +864,11 @@ static hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double a
     return hipGetLastError();
 }
 
-hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
-                       hipStream_t stream)
-{
-    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, stream)
-               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace,
-                                       stream);
-}
-
-size_t syrk_workspace_bytes(bool f32, const Plan& plan)
-{
-    return (size_t)plan.n_ws_blocks * (size_t)plan.ws_slices * 6 * 16 * kThreads * (f32 ? 4 : 8);
-}
-
 // The block shape is the one with the shortest estimated time on `units` compute units: rounds of
 // blocks, each costing its tiles (K columns at one unit's share of the MFMA peak) plus the fixed
 // cost of a block.  A product with few blocks per unit is cut finer so that the last round is full.
 template <typename T>
-static hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const void* R, int64_t ldr,
+hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const void* R, int64_t ldr,
                                 const void* Q, int64_t ldq, double beta, void* C, int64_t ldc, int units,
                                 hipStream_t stream)
 {
@@ -905,6 +896,42 @@ static hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, c
     return hipGetLastError();
 }
 
+// ---- translation units ---------------------------------------------------------------------------
+// The file is compiled several times in parallel (each kernel template with its many instances takes
+// minutes): -DTBS_UNIT_SYRK or -DTBS_UNIT_GEMM with -DTBS_UNIT_TYPE=double|float instantiates one
+// launcher (and the kernels it launches), -DTBS_UNIT_DISPATCH defines the entry points that choose
+// between them; without any of these macros one translation unit holds everything.
+#if defined(TBS_UNIT_SYRK)
+template hipError_t launch_syrk_t<TBS_UNIT_TYPE>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
+                                                 void*, int64_t, int, void*, hipStream_t);
+#elif defined(TBS_UNIT_GEMM)
+template hipError_t launch_gemm_t<TBS_UNIT_TYPE>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
+                                                 int64_t, double, void*, int64_t, int, hipStream_t);
+#else
+#if defined(TBS_UNIT_DISPATCH)
+extern template hipError_t launch_syrk_t<double>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
+                                                 void*, int64_t, int, void*, hipStream_t);
+extern template hipError_t launch_syrk_t<float>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
+                                                void*, int64_t, int, void*, hipStream_t);
+extern template hipError_t launch_gemm_t<double>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
+                                                 int64_t, double, void*, int64_t, int, hipStream_t);
+extern template hipError_t launch_gemm_t<float>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
+                                                int64_t, double, void*, int64_t, int, hipStream_t);
+#endif
+hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
+                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
+                       hipStream_t stream)
+{
+    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, stream)
+               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace,
+                                       stream);
+}
+
+size_t syrk_workspace_bytes(bool f32, const Plan& plan)
+{
+    return (size_t)plan.n_ws_blocks * (size_t)plan.ws_slices * 6 * 16 * kThreads * (f32 ? 4 : 8);
+}
+
 hipError_t launch_gemm_nt(bool f32, int64_t m, int64_t n, int64_t K, double alpha, const void* R,
                           int64_t ldr, const void* Q, int64_t ldq, double beta, void* C, int64_t ldc,
                           int units, hipStream_t stream)
@@ -912,5 +939,7 @@ hipError_t launch_gemm_nt(bool f32, int64_t m, int64_t n, int64_t K, double alph
     return f32 ? launch_gemm_t<float>(m, n, K, alpha, R, ldr, Q, ldq, beta, C, ldc, units, stream)
                : launch_gemm_t<double>(m, n, K, alpha, R, ldr, Q, ldq, beta, C, ldc, units, stream);
 }
+
+#endif
 
 }  // namespace tbs
