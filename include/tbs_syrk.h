@@ -11,11 +11,8 @@
  *                          triangular solve, Triangle Block trailing update.
  *
  * Conventions common to every call
- *   - All matrices are row-major with a leading dimension counted in elements.  Any leading
- *     dimension and alignment of A is accepted; the fast code path needs the rows of A (for the
- *     Cholesky factorisation: of the matrix) to start at multiples of 16 bytes (an even leading
- *     dimension in double precision, a multiple of 4 in single precision, and a base pointer aligned
- *     likewise); otherwise a slower path is taken (about two thirds of the throughput).
+ *   - All matrices are row-major with a leading dimension counted in elements; pointers need the
+ *     alignment of an element, leading dimensions need none.
  *   - Matrix pointers are DEVICE pointers; the caller owns them (and the stream) before, during
  *     and after the call.  The library allocates and frees no device memory.
  *   - Only entries on or below the diagonal (column <= row) of a symmetric / triangular matrix

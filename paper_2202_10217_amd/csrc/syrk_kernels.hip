@@ -336,7 +336,7 @@ struct SliceCtx {
 // the other LDS buffer, the workgroup synchronises, the first operands of the next chunk are read
 // and the chunk after that is requested from global memory, all hidden behind the last k-step's
 // MFMAs.
-//   FAST: the slots SLOTS are exactly the block's, 16-byte loads are legal and M >= KC (`ragged`: a
+//   FAST: the slots SLOTS are exactly the block's and M >= KC (`ragged`: a
 //   panel has fewer than 64 rows inside the matrix; the loop then reads its last row in place of the
 //   missing ones and the epilogue checks rows and columns).  The chunk loop over the whole chunks then has no
 //   test and no branch, so the accumulators stay in their registers across it; columns beyond the
@@ -649,7 +649,9 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
     constexpr int KC = Cfg<T>::KC;
     // the assembly loop addresses a panel's 64 rows with 32-bit byte offsets from the panel's start
     const int64_t lim = (int64_t)1 << 32;
-    const bool fast_ok = m.M >= KC && vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq) &&
+    // (rows need no alignment beyond that of an element: the loads into LDS take 16 bytes from any
+    // element-aligned address, at full speed)
+    const bool fast_ok = m.M >= KC &&
                          (int64_t)kTile * m.ldr * (int64_t)sizeof(T) < lim &&
                          (int64_t)kTile * m.ldq * (int64_t)sizeof(T) < lim;
     if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
