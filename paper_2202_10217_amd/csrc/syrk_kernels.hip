@@ -371,8 +371,6 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
         ld[p] = col_side ? m.ldq : m.ldr;
         nrows[p] = col_side ? m.nq : m.nr;
     }
-    Stager<T, NP, PANELS> st;
-    st.init(base, ld, nrows, prow, tid);
 
     acc_t acc[Shape::NSLOT][4];
 #pragma unroll
@@ -443,6 +441,8 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     auto checked_columns = [&](int k_begin) {
         const int nch = (M - k_begin + KC - 1) / KC;
         if (nch <= 0) return;
+        Stager<T, NP, PANELS> st;
+        st.init(base, ld, nrows, prow, tid);
         const bool aligned = vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq);
         st.load_checked(M, k_begin, aligned && k_begin + KC <= M, tid);
         st.store(lds, tid);
