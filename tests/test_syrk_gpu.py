@@ -343,3 +343,27 @@ def test_pinned_block_shapes_bit_exact_and_in_tolerance(tb, idx, monkeypatch):
     Cg = _run(tb, A, C0, -1.0, 1.0)
     Cref, D = _reference(A, C0, -1.0, 1.0)
     _check(Cg, C0, Cref, D, np.float64)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("N,M,pad,shift", [(1027, 100, 1, 1), (2051, 1031, 3, 0), (640, 4100, 1, 3), (4133, 200, 5, 1)])
+def test_edges_of_the_main_loop_bit_exact(tb, N, M, pad, shift, dtype):
+    # everything the main loop has to cope with at once: a last tile row with few rows, a contraction
+    # length that is no multiple of the chunk, rows that are only element-aligned (odd leading dimension,
+    # pointer off by `shift` elements); integer data, so the result must agree bit for bit
+    A = inputs.small_int_matrix(N, M, seed=N + 3 * M, dtype=dtype)
+    C0 = inputs.symmetric_uniform(N, seed=N + 1, dtype=dtype, int_range=(-7, 7))
+    tdt = torch.float64 if dtype == np.float64 else torch.float32
+    buf = torch.zeros(N * (M + pad) + 8, dtype=tdt, device="cuda")
+    Av = buf[shift:shift + N * (M + pad)].view(N, M + pad)[:, :M]
+    Av.copy_(_dev(A))
+    Cref = C0.astype(np.float64).copy()
+    oracle.syrk_lower(A.astype(np.float64), Cref, 2.0, -1.0)
+    il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+    for square in (False, True):
+        dC = _dev(C0)
+        (tb.tbs_syrk_lower_square if square else tb.tbs_syrk_lower)(Av, dC, 2.0, -1.0)
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy()
+        assert np.array_equal(out[il].astype(np.float64), Cref[il])
+        assert np.array_equal(out[iu], C0[iu])
