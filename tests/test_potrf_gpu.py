@@ -175,3 +175,40 @@ def test_calls_on_two_streams_without_waiting_in_between(tb):
             for d, G in zip(ds, Gs):
                 d.copy_(torch.from_numpy(G @ G.T).cuda())
             torch.cuda.synchronize()
+
+
+def test_calls_from_two_host_threads(tb):
+    # two host threads, each with its own stream and matrix, call at the same time (ctypes releases the
+    # interpreter lock during the call): the library enqueues one call after the other; exact factors
+    import threading
+    sizes = (2900, 3500)
+    rng = np.random.default_rng(29)
+    Gs, ds = [], []
+    for N in sizes:
+        G = np.tril(rng.integers(-1, 2, size=(N, N))).astype(np.float64)
+        np.fill_diagonal(G, rng.integers(1, 3, size=N))
+        Gs.append(G)
+        ds.append(torch.from_numpy(G @ G.T).cuda())
+    ws = [torch.empty(4096, dtype=torch.uint8, device="cuda") for _ in sizes]
+    streams = [torch.cuda.Stream() for _ in sizes]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            for _ in range(3):
+                info = tb.tbs_potrf_lower(ds[i], workspace=ws[i], stream=streams[i])   # synchronises its stream
+                if info != 0 or not np.array_equal(np.tril(ds[i].cpu().numpy()), Gs[i]):
+                    errors.append((i, info))
+                with torch.cuda.stream(streams[i]):
+                    ds[i].copy_(torch.from_numpy(Gs[i] @ Gs[i].T).cuda(), non_blocking=False)
+                streams[i].synchronize()
+        except Exception as e:                                  # noqa: BLE001 - reported below
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(len(sizes))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
