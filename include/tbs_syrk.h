@@ -59,9 +59,15 @@ const char* tbs_status_string(tbs_status s);
  *   calls that may run at the same time need different workspaces).  tbs_syrk_lower_workspace()
  *   reports what the library can use: 0 for most sizes.  For problems with few tiles per compute
  *   unit it is the room for blocks that are computed in parts along the contraction dimension (the
- *   parts are summed in a fixed order, results are reproducible).  With NULL or fewer bytes the
- *   call is still valid: the library then uses its plan without such blocks (same results up to
- *   the order of the floating-point sums, lower throughput).  tbs_syrk_lower_square ignores it.
+ *   parts are summed in a fixed order, results are reproducible).  With workspace == NULL the call
+ *   uses its plan without such blocks (same results up to the order of the floating-point sums,
+ *   lower throughput); a workspace that is not NULL must hold the reported number of bytes, else
+ *   TBS_EWORKSPACE is returned and nothing is launched.  tbs_syrk_lower_square ignores it.
+ *   The persistent form of the kernel and the blocks computed in parts count through small arrays
+ *   of device memory inside the library (file scope, no allocation).  A set of counters serves the
+ *   launches of one stream; if every set is held by launches of other streams that have not
+ *   finished (more than 64 streams busy at once), the call runs one workgroup per block without
+ *   blocks computed in parts instead: slower, same contract.
  * The schedule (Section 5.1.4): C is cut into b x b tiles (b = 64); the tile rows are grouped
  * into triangle blocks R^{i,j} = { u*c + f^{i,j}(u) } of k tile rows (an indexing family in the
  * sense of Section 5.1.1: the cyclic one of Section 5.1.2, or its XOR analogue for c = 2^m); one

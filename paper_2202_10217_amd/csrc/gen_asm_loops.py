@@ -35,7 +35,7 @@ reads, waits, scalar instructions and the barrier are free).  Hence:
     per 64 KB of the ring, set up once), the LDS target of a load is a constant added to M0;
   - the lanes' global offsets never change (they address a row inside a panel, so 32 bits suffice for
     matrices of any size); the scalar unit moves one pointer per panel one chunk on after each request
-    (fixed scalar registers, declared clobbered);
+    (fixed scalar registers, declared clobbered, as is M0);
   - rarely executed code (the waits near the end, the last k-step without a request) sits after the
     loop, so the steady state takes no branch except the back edge once per pass.
 
@@ -214,7 +214,7 @@ __device__ __forceinline__ void {name}(Cfg<{ty}>::acc_t (&acc)[6][4], const AsmL
           {ads},
           {gps},
           [nch] "s"(g.nch), [step] "s"(g.step), [m0b] "s"(g.m0base)
-        : "memory", "scc", {clob});
+        : "memory", "scc", "m0", {clob});
 }}
 """
     return name, fn

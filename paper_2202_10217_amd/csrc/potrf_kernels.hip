@@ -335,12 +335,6 @@ __global__ __launch_bounds__(256) void trsm_tile_kernel(int m, int nb, const T* 
 //   operand of the later tile columns, back to LDS.
 // The operations on an element are those of Algorithm 2 for the rows below a diagonal block, except
 // that the products of 64 columns are summed by the MFMA before they are subtracted.
-#ifdef TBS_TRACE
-__device__ unsigned long long g_panel_trace[8][6];      // measurement builds: phase times of workgroup 0
-#define PANEL_MARK(slot) do { if (blockIdx.x == 0 && tid == 0) g_panel_trace[jt][slot] = wall_clock64(); } while (0)
-#else
-#define PANEL_MARK(slot) do { } while (0)
-#endif
 constexpr int kPR = 32;                                    // rows of X per workgroup
 constexpr int kMaxPanelTiles = 8;                          // n <= 512
 constexpr int kXsLd = kPT * (kMaxPanelTiles - 1) + 2;      // LDS row of solved tiles (padded)
@@ -375,7 +369,6 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* 
     for (int jt = 0; jt < nt; ++jt) {
         const int c0 = jt * kPT;
         const int nbw = min(kPT, n - c0);
-        PANEL_MARK(0);
         // requests to global memory, in the order in which their data is needed (they complete in
         // order): the first operand values of L, the diagonal tile L[jt][jt] (written to LDS after the
         // products), the next tile of X
@@ -426,7 +419,6 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* 
 #pragma unroll
             for (int s4 = 0; s4 < 16; ++s4) bcur[s4] = bnxt[s4];
         }
-        PANEL_MARK(1);
 #pragma unroll
         for (int rg = 0; rg < 2; ++rg)
 #pragma unroll
@@ -451,7 +443,6 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* 
             rdg[tid] = T(1) / d;
         }
         __syncthreads();
-        PANEL_MARK(2);
         if (tid < 4 * kPR) {                                // two wavefronts: four lanes per row
             const int i = tid >> 2, q = tid & 3;
             T* br = Xs + i * kXsLd + place * kPT;
@@ -462,7 +453,6 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* 
                 cur[c] = Lq[q * 16 + c];
             }
             TrsmSteps<T, 1, 0>::run(b, cur, dg[0], rdg[0], Lq, dg, rdg, q);
-            PANEL_MARK(3);
             const int64_t row = row0 + i;
 #pragma unroll
             for (int c = 0; c < 16; ++c) {
@@ -472,7 +462,6 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(int m, int n, const T* 
             }
         }
         __syncthreads();
-        PANEL_MARK(4);
     }
 }
 

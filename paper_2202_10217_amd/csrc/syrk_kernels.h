@@ -7,15 +7,33 @@
 
 namespace tbs {
 
+constexpr int kSliceCounters = 512;      // cut blocks per plan (one device counter each)
+
+// The device counters one launch may use: the pair of the persistent form, the counters of the cut
+// blocks, and the event that completes with the launch.  Empty (all null): none could be given.
+struct CounterLease {
+    unsigned int* ctr = nullptr;
+    unsigned int* slice_ctr = nullptr;
+    hipEvent_t done = nullptr;
+};
+
+// Counters for the next launch on `stream` on the current device.  Launches on one stream share a
+// set (they run one after the other); another stream gets a set of its own, or one whose last launch
+// has finished; if every set belongs to a launch that may still be running, *out stays empty and the
+// caller must launch the form that needs none (max_workgroups <= 0 and a plan without cut blocks).
+// Calls no allocation routine except for one event per set, created when the set is first handed out.
+hipError_t acquire_counters(hipStream_t stream, CounterLease* out);
+
 // C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`.  All pointers are device pointers; sizes
 // have been validated by the caller.  max_workgroups > 0 bounds the launch: a plan with more blocks
 // runs as that many persistent workgroups taking blocks in list order (normally the number of
 // compute units; fewer leaves units free for kernels of other streams); <= 0: one workgroup per block.
+// The persistent form and plans with cut blocks need a lease from acquire_counters (same stream).
 // A plan with sliced blocks needs `workspace`: device memory of syrk_workspace_bytes(), aligned to the
 // element size, contents arbitrary; it is only written and read by this launch.
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
                        int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
-                       hipStream_t stream);
+                       const CounterLease& lease, hipStream_t stream);
 size_t syrk_workspace_bytes(bool f32, const Plan& plan);
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, all row-major device matrices that do not

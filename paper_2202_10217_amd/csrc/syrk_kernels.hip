@@ -12,12 +12,14 @@
 //   * a diagonal tile: one panel, only the 10 of 16 sub-tiles on or below the diagonal.
 // Within a tile, wavefront w owns the 16-column strip w: 4 MFMA sub-tiles of 16 x 16 per tile.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <cstdlib>
 #include <stdint.h>
 
 #include <atomic>
 #include <mutex>
 
+#include "counter_slots.h"
 #include "tbs_plan.h"
 #include "syrk_kernels.h"
 
@@ -251,20 +253,6 @@ __device__ __forceinline__ void mfma_step(const Operands<T, Shape, SLOTS>& op,
             }
 }
 
-#ifdef TBS_TRACE
-// measurement builds only: summed time (100 MHz ticks) inside the chunk loop [0], inside the epilogue
-// [1], number of blocks [2]
-__device__ unsigned long long g_phase[4];
-extern "C" int tbs_phase_fetch(unsigned long long* host, int reset)
-{
-    int e = (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 4);
-    if (reset) {
-        unsigned long long z[4] = {0, 0, 0, 0};
-        e |= (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase), z, sizeof(z));
-    }
-    return e;
-}
-#endif
 
 // ---- the main loop in assembly (generated) -----------------------------------------------------
 struct AsmLoopArgs {
@@ -355,9 +343,6 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     typedef typename Cfg<T>::acc_t acc_t;
     typedef Operands<T, Shape, SLOTS> Ops;
     const int tid = threadIdx.x;
-#ifdef TBS_TRACE
-    unsigned long long phase_mark = 0;
-#endif
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
@@ -424,17 +409,7 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                 go[q++] = (uint32_t)(row * ld[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
             }
         }
-#ifdef TBS_TRACE
-        const unsigned long long t_loop0 = wall_clock64();
-#endif
         AsmLoop<T, Shape, SLOTS>::run(acc, g, go);
-#ifdef TBS_TRACE
-        if (tid == 0) {
-            phase_mark = wall_clock64();
-            atomicAdd(&g_phase[0], phase_mark - t_loop0);
-            atomicAdd(&g_phase[2], 1ull);
-        }
-#endif
     }
     // The checked loop over the columns [k_begin, M) (everything, or what the assembly loop left over):
     // two padded LDS buffers, chunks staged through registers, every access checked.
@@ -558,9 +533,6 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
                                               ((dmask >> sl) & 1u) != 0);
                 }
         }
-#ifdef TBS_TRACE
-        if (tid == 0) atomicAdd(&g_phase[1], wall_clock64() - phase_mark);
-#endif
     } else {
 #pragma unroll
         for (int i = 0; i < Shape::NA; ++i)
@@ -729,15 +701,6 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, in
 // (A variant with one queue per accelerator die, each holding blocks that share panels of A, was
 // measured and dropped: the bytes fetched into the L2s did not change.  The workgroups of a die
 // drift apart by more chunks than its 4 MB L2 can hold for 28 blocks with six chunks in flight each.)
-#ifdef TBS_TRACE
-// measurement builds only: start and end time (100 MHz wall clock) and place of every block
-constexpr int kTraceItems = 1 << 16;
-__device__ unsigned long long g_trace[kTraceItems][3];
-extern "C" int tbs_trace_fetch(unsigned long long* host, int n_items)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(unsigned long long) * 3 * (size_t)n_items);
-}
-#endif
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, int N, int M, T alpha,
@@ -757,17 +720,7 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
         __syncthreads();
         const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
         if (id >= plan.n_items) break;
-#ifdef TBS_TRACE
-        const unsigned long long t_start = wall_clock64();
-#endif
         run_item<T>(plan, id, m, reinterpret_cast<T*>(smem), sp);
-#ifdef TBS_TRACE
-        if (threadIdx.x == 0 && id < kTraceItems) {
-            g_trace[id][0] = t_start;
-            g_trace[id][1] = wall_clock64();
-            g_trace[id][2] = (unsigned long long)blockIdx.x << 8;
-        }
-#endif
     }
     if (threadIdx.x == 0) {
         __threadfence();
@@ -778,15 +731,6 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
         }
     }
 }
-
-// Counter pairs for persistent launches, zero at load time and zero again after every launch.
-// Launches that may run at the same time must use different pairs: they are handed out round robin.
-constexpr int kCounterPairs = 64;
-static __device__ unsigned int g_syrk_counters[kCounterPairs][2];
-// Counters of the sliced blocks of a launch (parts finished), one set per launch in flight, handed
-// out like the pairs above; zero at load time, set back to zero by the workgroup that sums a block.
-constexpr int kSliceCounters = 512;
-static __device__ unsigned int g_slice_counters[kCounterPairs][kSliceCounters];
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, rectangular blocks of mr x nc tiles
 // (mr <= 2, nc <= 3), one workgroup per block.
@@ -818,51 +762,27 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
     run_block<T, RectShape, false>(it, m, lds, SliceCtx<T>{});
 }
 
+// `lease`: the counters of this launch (see acquire_counters); needed by the persistent form and by
+// plans with cut blocks.  Its event, if any, is attached to the kernel: it completes with the launch.
 template <typename T>
 hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
                                 int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* ws,
-                                hipStream_t stream)
+                                const CounterLease& lease, hipStream_t stream)
 {
     if (plan.n_items <= 0) return hipSuccess;
     if (plan.n_ws_blocks > kSliceCounters || (plan.n_ws_blocks > 0 && ws == nullptr)) return hipErrorInvalidValue;
     const bool persistent = max_workgroups > 0 && plan.n_items > max_workgroups;
-    unsigned int* ctr = nullptr;
-    unsigned int* slice_ctr = nullptr;
-    if (persistent || plan.n_ws_blocks > 0) {
-        // addresses of the counter arrays on the current device, looked up once per device
-        static std::mutex mu;
-        static unsigned int* base[64] = {nullptr};
-        static unsigned int* sbase[64] = {nullptr};
-        static std::atomic<unsigned> next_pair{0};
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        {
-            std::lock_guard<std::mutex> lock(mu);
-            if (!base[dev]) {
-                void* ptr = nullptr;
-                e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_syrk_counters));
-                if (e != hipSuccess) return e;
-                void* sptr = nullptr;
-                e = hipGetSymbolAddress(&sptr, HIP_SYMBOL(g_slice_counters));
-                if (e != hipSuccess) return e;
-                base[dev] = static_cast<unsigned int*>(ptr);
-                sbase[dev] = static_cast<unsigned int*>(sptr);
-            }
-        }
-        const unsigned pair = next_pair.fetch_add(1) % kCounterPairs;
-        ctr = base[dev] + 2 * pair;
-        slice_ctr = sbase[dev] + (size_t)kSliceCounters * pair;
-    }
+    if ((persistent && lease.ctr == nullptr) || (plan.n_ws_blocks > 0 && lease.slice_ctr == nullptr))
+        return hipErrorInvalidValue;
     if (!persistent) {
-        hipLaunchKernelGGL(tbs_syrk_kernel<T>, dim3((unsigned)plan.n_items), dim3(kThreads), 0, stream, plan,
-                           (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc, (T*)ws, slice_ctr);
+        hipExtLaunchKernelGGL(tbs_syrk_kernel<T>, dim3((unsigned)plan.n_items), dim3(kThreads), 0, stream, nullptr,
+                              lease.done, 0, plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc,
+                              (T*)ws, lease.slice_ctr);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(tbs_syrk_persistent_kernel<T>, dim3((unsigned)max_workgroups), dim3(kThreads), 0, stream,
-                       plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc, ctr, (T*)ws,
-                       slice_ctr);
+    hipExtLaunchKernelGGL(tbs_syrk_persistent_kernel<T>, dim3((unsigned)max_workgroups), dim3(kThreads), 0, stream,
+                          nullptr, lease.done, 0, plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C,
+                          ldc, lease.ctr, (T*)ws, lease.slice_ctr);
     return hipGetLastError();
 }
 
@@ -905,27 +825,88 @@ hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const vo
 // between them; without any of these macros one translation unit holds everything.
 #if defined(TBS_UNIT_SYRK)
 template hipError_t launch_syrk_t<TBS_UNIT_TYPE>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
-                                                 void*, int64_t, int, void*, hipStream_t);
+                                                 void*, int64_t, int, void*, const CounterLease&, hipStream_t);
 #elif defined(TBS_UNIT_GEMM)
 template hipError_t launch_gemm_t<TBS_UNIT_TYPE>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
                                                  int64_t, double, void*, int64_t, int, hipStream_t);
 #else
 #if defined(TBS_UNIT_DISPATCH)
 extern template hipError_t launch_syrk_t<double>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
-                                                 void*, int64_t, int, void*, hipStream_t);
+                                                 void*, int64_t, int, void*, const CounterLease&, hipStream_t);
 extern template hipError_t launch_syrk_t<float>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
-                                                void*, int64_t, int, void*, hipStream_t);
+                                                void*, int64_t, int, void*, const CounterLease&, hipStream_t);
 extern template hipError_t launch_gemm_t<double>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
                                                  int64_t, double, void*, int64_t, int, hipStream_t);
 extern template hipError_t launch_gemm_t<float>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
                                                 int64_t, double, void*, int64_t, int, hipStream_t);
 #endif
+// ---- counters in device memory --------------------------------------------------------------------
+// One set per slot: ctr[2] of the persistent form (next block, workgroups done) and one counter per
+// cut block (parts finished).  All zero at load time; every launch leaves its set zero again (the last
+// workgroup of a persistent launch resets the pair, the workgroup that sums a block resets its
+// counter).  Which launch may use which slot is decided by SlotTable (counter_slots.h); the event of a
+// slot completes with the last launch that used it.
+static __device__ unsigned int g_syrk_counters[kCounterSlots][2];
+static __device__ unsigned int g_slice_counters[kCounterSlots][kSliceCounters];
+
+namespace {
+struct DeviceCounters {
+    unsigned int* pairs = nullptr;      // device address of g_syrk_counters on this device
+    unsigned int* slices = nullptr;     // ... of g_slice_counters
+    hipEvent_t done[kCounterSlots] = {};
+    SlotTable table;
+};
+constexpr int kMaxDevices = 64;
+std::mutex g_counters_mu;
+DeviceCounters g_counters[kMaxDevices];
+}  // namespace
+
+hipError_t acquire_counters(hipStream_t stream, CounterLease* out)
+{
+    *out = CounterLease{};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_counters_mu);
+    DeviceCounters& dc = g_counters[dev];
+    if (!dc.pairs) {                                        // once per device, with that device current
+        void* ptr = nullptr;
+        void* sptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_syrk_counters));
+        if (e != hipSuccess) return e;
+        e = hipGetSymbolAddress(&sptr, HIP_SYMBOL(g_slice_counters));
+        if (e != hipSuccess) return e;
+        dc.slices = static_cast<unsigned int*>(sptr);
+        dc.pairs = static_cast<unsigned int*>(ptr);
+    }
+    SlotOwner who;
+    who.stream = stream;
+    if (stream == hipStreamPerThread) {                     // one handle, a different stream in every thread
+        static thread_local char tag;
+        who.thread = (uint64_t)reinterpret_cast<uintptr_t>(&tag);
+    }
+    const int s = dc.table.acquire(who, [&](int slot) {
+        return dc.done[slot] == nullptr || hipEventQuery(dc.done[slot]) == hipSuccess;
+    });
+    if (s < 0) return hipSuccess;                           // none free: out stays empty
+    if (!dc.done[s]) {
+        e = hipEventCreateWithFlags(&dc.done[s], hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+    }
+    out->ctr = dc.pairs + 2 * s;
+    out->slice_ctr = dc.slices + (size_t)kSliceCounters * s;
+    out->done = dc.done[s];
+    return hipSuccess;
+}
+
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
                        int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
-                       hipStream_t stream)
+                       const CounterLease& lease, hipStream_t stream)
 {
-    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, stream)
-               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace,
+    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, lease,
+                                      stream)
+               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, lease,
                                        stream);
 }
 

@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <map>
 #include <mutex>
+#include <string>
 #include <tuple>
 #include <utility>
 
@@ -40,6 +41,21 @@ int32_t compute_units()
     return ncu;
 }
 
+// The environment variables that change what the planner builds (all optional, for measurements).
+// They are read at every call and are part of the cache key, so a plan built under one setting is
+// never handed out under another.
+struct PlanEnv {
+    std::string costs, family, slices, tuning;
+    static PlanEnv read()
+    {
+        auto get = [](const char* name) {
+            const char* v = std::getenv(name);
+            return std::string(v ? v : "");
+        };
+        return PlanEnv{get("TBS_PLAN_COSTS"), get("TBS_PLAN_FAMILY"), get("TBS_SYRK_SLICES"), get("TBS_PLAN_TUNING")};
+    }
+};
+
 // A plan depends on the number of tile rows and, for small matrices, on how long a tile takes
 // compared with the fixed cost of a block (prologue, epilogue, dispatch: about 20 us against
 // M * 2 * 64 * 64 flops at one compute unit's share of the MFMA peak), which decides how finely the
@@ -47,21 +63,25 @@ int32_t compute_units()
 const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M, bool sliced)
 {
     static std::mutex mu;
-    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool>, tbs::Plan> cache;
+    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool, std::string, std::string, std::string, std::string>,
+                    tbs::Plan>
+        cache;
     int32_t bucket = 0;
     while (bucket < 30 && ((int64_t)3 << bucket) / 2 <= M) ++bucket;     // M ~ 2^bucket
+    const PlanEnv env = PlanEnv::read();
     std::lock_guard<std::mutex> lock(mu);
-    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket, sliced);
+    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket, sliced, env.costs, env.family, env.slices,
+                               square ? std::string() : env.tuning);
     auto it = cache.find(key);
     if (it == cache.end()) {
         const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
         // fixed costs: a block (prologue, epilogue, taking it from the list), a part of a cut block, and
         // per part of the block again for summing them (TBS_PLAN_COSTS="block_us,part_us,per_part_us"
-        // overrides them, for measurements)
+        // overrides them)
         double block_us = 20.0, slice_us = 0.03 * tile_us, per_part_us = 0.0;
-        if (const char* c = std::getenv("TBS_PLAN_COSTS")) {
+        if (!env.costs.empty()) {
             double b = 0.0, sl = 0.0, pp = 0.0;
-            if (std::sscanf(c, "%lf,%lf,%lf", &b, &sl, &pp) >= 2 && b >= 0.0 && sl >= 0.0 && pp >= 0.0) {
+            if (std::sscanf(env.costs.c_str(), "%lf,%lf,%lf", &b, &sl, &pp) >= 2 && b >= 0.0 && sl >= 0.0 && pp >= 0.0) {
                 block_us = b;
                 slice_us = sl;
                 per_part_us = pp;
@@ -70,20 +90,17 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
         const double overhead_tiles = block_us / tile_us;
         tbs::Plan p;
         // TBS_PLAN_FAMILY=cyclic: the paper's cyclic family only (no power-of-two moduli)
-        const char* famenv = std::getenv("TBS_PLAN_FAMILY");
-        const bool xor_family = !(famenv && famenv[0] == 'c');
+        const bool xor_family = !(!env.family.empty() && env.family[0] == 'c');
         // blocks may be cut along the contraction dimension while a part keeps at least 8 chunks of
         // the smallest M of the bucket; TBS_SYRK_SLICES=0 turns that off, "levels,rows,...,tri,rect,
         // tail_blocks,tail" in TBS_PLAN_TUNING pins it
-        const char* slenv = std::getenv("TBS_SYRK_SLICES");
         const int64_t kc = dtype == TBS_F32 ? 32 : 16;
         const int64_t m_low = ((int64_t)3 << bucket) / 4;
         int32_t max_slices = (int32_t)std::min<int64_t>(tbs::kMaxSlices, m_low / (8 * kc));
-        if (!sliced || square || (slenv && slenv[0] == '0')) max_slices = 1;
+        if (!sliced || square || (!env.slices.empty() && env.slices[0] == '0')) max_slices = 1;
         // TBS_PLAN_TUNING="levels,rows,cols,base,zone_rows,zone_cols[,tri,rect,tail_blocks,tail]" pins
-        // the tuning the planner would otherwise choose (for measurements; every tuning covers each
-        // tile exactly once)
-        const char* pin = square ? nullptr : std::getenv("TBS_PLAN_TUNING");
+        // the tuning the planner would otherwise choose (every tuning covers each tile exactly once)
+        const char* pin = (square || env.tuning.empty()) ? nullptr : env.tuning.c_str();
         int lv = 0, mr = 0, nc = 0, base = 0, mrd = 0, ncd = 0, st = 1, sr = 1, tb = 0, ts = 1;
         if (pin && std::sscanf(pin, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &lv, &mr, &nc, &base, &mrd, &ncd, &st, &sr, &tb,
                                &ts) >= 4 &&
@@ -115,19 +132,25 @@ tbs_status check_syrk(tbs_dtype dtype, int64_t N, int64_t M, const void* A, int6
     return TBS_OK;
 }
 
-// The plan a call uses: the one with sliced blocks if the caller's workspace holds its parts, else the
-// one without.
-const tbs::Plan* plan_for_call(int32_t T, bool square, tbs_dtype dtype, int64_t M, const void* workspace,
-                               size_t workspace_bytes)
+// The plan a call uses: the one with cut blocks if the caller gave a workspace (which must then hold
+// its parts), else the one without.
+tbs_status plan_for_call(int32_t T, bool square, tbs_dtype dtype, int64_t M, const void* workspace,
+                         size_t workspace_bytes, const tbs::Plan** out)
 {
     const size_t es = dtype == TBS_F32 ? 4 : 8;
+    *out = nullptr;
+    if (workspace == nullptr || square) {
+        *out = cached_plan(T, square, dtype, M, false);
+        return *out ? TBS_OK : TBS_EINVAL;
+    }
     const tbs::Plan* sliced = cached_plan(T, square, dtype, M, true);
-    if (!sliced) return nullptr;
-    if (sliced->n_ws_blocks == 0) return sliced;
-    const size_t need = tbs::syrk_workspace_bytes(dtype == TBS_F32, *sliced);
-    if (workspace != nullptr && workspace_bytes >= need && (reinterpret_cast<uintptr_t>(workspace) % es) == 0)
-        return sliced;
-    return cached_plan(T, square, dtype, M, false);
+    if (!sliced) return TBS_EINVAL;
+    if (sliced->n_ws_blocks > 0) {
+        if (workspace_bytes < tbs::syrk_workspace_bytes(dtype == TBS_F32, *sliced)) return TBS_EWORKSPACE;
+        if ((reinterpret_cast<uintptr_t>(workspace) % es) != 0) return TBS_EINVAL;
+    }
+    *out = sliced;
+    return TBS_OK;
 }
 
 tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,
@@ -136,8 +159,9 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
 {
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = plan_for_call(T, square, dtype, M, workspace, workspace_bytes);
-    if (!plan) return TBS_EINVAL;
+    const tbs::Plan* plan = nullptr;
+    const tbs_status ps = plan_for_call(T, square, dtype, M, workspace, workspace_bytes, &plan);
+    if (ps != TBS_OK) return ps;
     static const bool persistent = [] {
         const char* v = std::getenv("TBS_SYRK_PERSISTENT");
         return !(v && v[0] == '0');
@@ -148,9 +172,20 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
         const long n = v ? std::atol(v) : 0;
         return (n > 0 && n < 4096) ? (int)n : 0;
     }();
-    const int wgs = persistent ? std::max(1, compute_units() - std::max(reserve_units, env_reserve)) : 0;
+    int wgs = persistent ? std::max(1, compute_units() - std::max(reserve_units, env_reserve)) : 0;
+    tbs::CounterLease lease;
+    if ((wgs > 0 && plan->n_items > wgs) || plan->n_ws_blocks > 0) {
+        if (tbs::acquire_counters(stream, &lease) != hipSuccess) return TBS_EHIP;
+        if (!lease.ctr) {
+            // every set of counters belongs to a launch on another stream that may still be running:
+            // the form that needs none (one workgroup per block, no cut blocks)
+            plan = cached_plan(T, square, dtype, M, false);
+            if (!plan) return TBS_EINVAL;
+            wgs = 0;
+        }
+    }
     const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, wgs,
-                                          workspace, stream);
+                                          workspace, lease, stream);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 

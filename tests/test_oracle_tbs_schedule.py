@@ -192,6 +192,31 @@ def test_tbs_volume_against_the_cost_formula():
     assert abs(io_sq.A - ts.square_A_volume(N, M, s)) <= 2 * N * M
 
 
+@pytest.mark.parametrize("k,c", [(4, 35), (5, 23), (6, 25)])
+def test_total_volume_theorem_of_the_element_granular_scheme(k, c):
+    # Theorem of Section 5.1.3 with its S = k(k+1)/2 (the k(k-1)/2 entries of a triangle block plus one
+    # column of A restricted to R): the replay of Algorithm 4 (b = 1) loads C exactly once and an amount
+    # of A between the lower bound N^2 M / (sqrt(2) sqrt(S)) and N^2 M / (k-1) + O(N M log N), whose
+    # ratio is sqrt(k(k+1)) / (k-1) (the theorem's "k - 1 ~ sqrt(2 S)").  tbs_volume_leading is that
+    # theorem's right-hand side without the O() term: a dropped sqrt(2), a swapped S or a wrong C term
+    # moves it out of the bracket below.
+    N, M = k * c, 3
+    A = inputs.small_int_matrix(N, M, seed=k)
+    C = np.zeros((N, N))
+    io = ts.tbs_syrk(A, C, k, 1)
+    S = k * (k + 1) // 2
+    assert io.C == N * (N + 1) // 2
+    lead = ts.tbs_volume_leading(N, M, S)
+    assert abs((lead - N * N / 2.0) - ts.syrk_lower_bound(N, M, S)) < 1e-9 * lead
+    total = io.A + io.C
+    lower_order = 4 * k * N * M * math.log2(N)
+    assert lead - N <= total + N                           # never below the bound (the diagonal's N/2 aside)
+    assert total <= lead * math.sqrt(k * (k + 1.0)) / (k - 1.0) + lower_order
+    # and the leading coefficient is the right one: the top-level blocks alone are N^2 M / k
+    assert io.A_q1 == c * c * k * M == N * N * M // k
+    assert ts.syrk_lower_bound(N, M, S) < io.A_q1 * (k / (k - 1.0))
+
+
 # ---- closed forms --------------------------------------------------------------------------------
 
 def test_bound_arithmetic():

@@ -91,11 +91,12 @@ TUNINGS = ["0,2,3,0", "0,1,1,0", "1,2,3,0,1,3", "1,1,3,0,1,2", "1,2,2,0,1,1", "2
 @pytest.mark.parametrize("idx", range(len(TUNINGS)))
 def test_every_pinned_tuning_covers_the_triangle_exactly_once(idx, monkeypatch):
     # the planner's candidates (levels, rectangle shape, base zones as triangle blocks, shape inside
-    # triangular regions), pinned through the environment; a size of its own per tuning, because the
-    # library keeps one plan per size
+    # triangular regions), pinned through the environment (the string is part of the plan-cache key,
+    # so the sizes may be the same for every tuning: 1600 is used by all of them on purpose)
+    from _plan_util import assert_plan_is_pinned
     monkeypatch.setenv("TBS_PLAN_TUNING", TUNINGS[idx])
-    for N in (4096 + 64 * (idx + 1), 1500 + 64 * idx, 64 * (idx + 1) - 5):
-        items = tb.tbs_syrk_lower_enumerate(tb.TBS_F32, N, 777)
+    for N in (4096 + 64 * (idx + 1), 1600, 64 * (idx + 1) - 5):
+        items, _ = assert_plan_is_pinned(tb, tb.TBS_F32, N, 777, TUNINGS[idx])
         T = (N + B - 1) // B
         count = np.zeros((T, T), dtype=np.int32)
         for r, q in _tiles_of(items):

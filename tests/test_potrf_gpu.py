@@ -97,19 +97,21 @@ def test_fp32(tb):
 
 
 def _probe_check(L, S0):
-    """||L (L^T x) - A x|| / (||A||_F ||x||) for a few random x, and exact rows of L L^T for a sample of
-    rows, in float64 on the host (the N^3/3-flop residual is too slow there at these sizes)."""
+    """Necessary conditions of the bar that are cheap at any size, in float64 on the host:
+    ||L (L^T x) - A x|| / ||A x|| <= 1e-13 for a few random x, and, for a sample of rows i, every entry
+    (L L^T)_ij within 1e-13 (|L| |L|^T)_ij of A_ij (the componentwise form of the bar)."""
     N = S0.shape[0]
     x = inputs.normal_matrix(N, 4, seed=17)
-    r = L @ (L.T @ x) - S0 @ x
-    nrmA = np.linalg.norm(S0)
-    rel = np.linalg.norm(r, axis=0) / (nrmA * np.linalg.norm(x, axis=0))
-    assert rel.max() <= 1e-13
-    rows = np.unique(np.clip(np.array([0, 1, 63, 64, 511, 512, 513, 5000, 6143, 6144, 6500, 8191, 8192, 12345,
-                                       N - 2, N - 1]), 0, N - 1))
+    Ax = S0 @ x
+    r = L @ (L.T @ x) - Ax
+    rel = np.linalg.norm(r, axis=0) / np.linalg.norm(Ax, axis=0)
+    assert rel.max() <= 1e-13, rel
+    rows = np.unique(np.clip(np.array([0, 1, 63, 64, 511, 512, 513, 1023, 1024, 1025, 5000, 6143, 6144, 6500,
+                                       8191, 8192, 12345, N - 2, N - 1]), 0, N - 1))
     rec = L[rows] @ L.T                                      # rows of L L^T
-    for rr, line in zip(rows, rec):
-        assert np.abs(line[:rr + 1] - S0[rr, :rr + 1]).max() <= 1e-13 * nrmA / np.sqrt(N) * 50
+    bound = np.abs(L[rows]) @ np.abs(L).T
+    for rr, line, bd in zip(rows, rec, bound):
+        assert (np.abs(line[:rr + 1] - S0[rr, :rr + 1]) <= 1e-13 * bd[:rr + 1]).all(), rr
 
 
 @pytest.mark.parametrize("N", [7000, 9001])
@@ -136,19 +138,59 @@ def test_exact_integer_factor_with_look_ahead(tb):
     assert np.array_equal(np.tril(out), G)
 
 
-def test_config4_n16384_probe_residual(tb):
-    # full size: the N^3/3-flop residual is too slow on the host; use random probes
-    #   ||L (L^T x) - A x|| / (||A||_F ||x||)  for a few x, and the exact columns of L L^T for a
-    # sample of rows, all in float64 on the host.
+def test_config4_n16384_residual_in_full(tb):
+    # the stated bar at the full size: ||L L^T - A||_F / ||A||_F <= 1e-13 with every entry of L L^T
+    # evaluated by the oracle (sums in extended precision; about N^3/6 multiply-adds on the host cores),
+    # and the cheap probes besides
     N = 16384
     S0 = inputs.spd_diag_dominant(N, seed=3)
     d = torch.from_numpy(S0).cuda()
     info = tb.tbs_potrf_lower(d)
     torch.cuda.synchronize()
     assert info == 0
-    L = np.tril(d.cpu().numpy())
+    out = d.cpu().numpy()
     del d
+    for r in (0, 1, 5000, N - 2):                           # nothing above the diagonal was written
+        assert np.array_equal(out[r, r + 1:], S0[r, r + 1:])
+    L = np.tril(out)
+    del out
+    assert (np.diag(L) > 0).all()
     _probe_check(L, S0)
+    res = oracle.llt_residual(L, S0)
+    assert res <= 1e-13, res
+
+
+# Panels twice as wide are used while the trailing matrix has at least TBS_POTRF_WIDE_ROWS rows (8192 by
+# default; read at every call): with a small value, matrices the oracle factors in seconds take that path,
+# alone (all panels 1024 wide) or followed by 512-wide panels (the switch between the two).
+@pytest.mark.parametrize("N,wide_rows", [(3600, 512), (3500, 1800), (4133, 2100)])
+def test_double_width_panels_against_the_oracle(tb, N, wide_rows, monkeypatch):
+    monkeypatch.setenv("TBS_POTRF_WIDE_ROWS", str(wide_rows))
+    S0 = inputs.spd_diag_dominant(N, seed=N)
+    S = S0.copy()
+    S[np.triu_indices(N, 1)] = np.nan                       # the upper triangle must not be referenced
+    info, out = _factor(tb, S)
+    assert info == 0
+    iu, il = np.triu_indices(N, 1), np.tril_indices(N)
+    assert np.isnan(out[iu]).all(), "upper triangle was modified"
+    Lo = S0.copy()
+    assert oracle.potrf_lower(Lo) == 0
+    L = np.tril(out)
+    assert oracle.llt_residual(L, S0) <= 1e-13
+    assert np.abs(L[il] - Lo[il]).max() <= 1e-12 * np.abs(Lo[il]).max()
+
+
+@pytest.mark.parametrize("N,wide_rows", [(3700, 512), (4000, 2000)])
+def test_double_width_panels_recover_an_integer_factor_exactly(tb, N, wide_rows, monkeypatch):
+    monkeypatch.setenv("TBS_POTRF_WIDE_ROWS", str(wide_rows))
+    rng = np.random.default_rng(N)
+    G = np.tril(rng.integers(-1, 2, size=(N, N))).astype(np.float64)
+    np.fill_diagonal(G, rng.integers(1, 3, size=N))
+    S = G @ G.T
+    info, out = _factor(tb, S)
+    assert info == 0
+    assert np.array_equal(np.tril(out), G)
+    assert np.array_equal(out[np.triu_indices(N, 1)], S[np.triu_indices(N, 1)])
 
 
 def test_calls_on_two_streams_without_waiting_in_between(tb):

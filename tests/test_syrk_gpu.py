@@ -189,43 +189,125 @@ def test_empty_problem(tb):
     torch.cuda.synchronize()
 
 
-def _sampled_check(tb, name, nsample, dtype, full_rows=None):
+def _check_full_in_row_bands(Cg, C0, Cref, D, dtype, band=1024):
+    """The stated bar on every entry of the lower triangle, and bit-for-bit equality above the diagonal,
+    band by band (the index arrays of a whole 16384 x 16384 triangle would not be worth their memory)."""
+    N = Cg.shape[0]
+    worst = 0.0
+    cols = np.arange(N)
+    for r0 in range(0, N, band):
+        r1 = min(N, r0 + band)
+        low = cols[None, :r1] <= np.arange(r0, r1)[:, None]
+        g, c0 = Cg[r0:r1, :r1], C0[r0:r1, :r1]
+        assert np.array_equal(g[~low], c0[~low]) and np.array_equal(Cg[r0:r1, r1:], C0[r0:r1, r1:]), \
+            "upper triangle was modified"
+        err = np.abs(g.astype(np.float64) - Cref[r0:r1, :r1])[low]
+        den = np.maximum(D[r0:r1, :r1][low], np.finfo(np.float64).tiny)
+        worst = max(worst, float((err / den).max()))
+    assert worst <= TOL[dtype], f"componentwise error {worst:.3e}"
+    return worst
+
+
+def _full_check(tb, name):
+    """Every entry of the result at the configuration's full size against the oracle with the
+    extended-precision sum (Algorithm 1 as plain loops), in the launch configuration bench.py times:
+    the library's workspace is passed, so the plan is the one with blocks cut along the contraction
+    dimension where the library uses them."""
+    _, A, C0, alpha, beta = inputs.make_config(name)
+    N, M = A.shape
+    code = tb.TBS_F64
+    need = tb.tbs_syrk_lower_workspace(code, N, M)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else False
+    dA, dC = _dev(A), _dev(C0)
+    tb.tbs_syrk_lower(dA, dC, alpha, beta, workspace=ws)
+    torch.cuda.synchronize()
+    Cg = dC.cpu().numpy()
+    del dC
+    Cref = C0.copy()
+    oracle.syrk_lower(A, Cref, alpha, beta, extended=True)
+    D = np.abs(beta) * np.abs(C0)
+    oracle.syrk_lower(np.abs(A), D, abs(alpha), 1.0, extended=True)
+    return _check_full_in_row_bands(Cg, C0, Cref, D, np.float64)
+
+
+def test_config2_n4096_m4096_every_entry(tb):
+    _full_check(tb, "syrk_n4096_m4096_f64")
+
+
+def test_config3_n16384_m512_every_entry(tb):
+    _full_check(tb, "syrk_n16384_m512_f64")
+
+
+def _tiles_by_block_kind(items):
+    """Tiles (row tile, column tile) of the work list, by the kind of block that computes them:
+    'tri' (triangle blocks of an indexing family or of a base zone), 'rect' (rectangles strictly below
+    the diagonal), 'rect_diag' (off-diagonal tiles of rectangles that carry diagonal tiles), 'diag'."""
+    out = {"tri": [], "rect": [], "rect_diag": [], "diag": []}
+    for row in items.tolist():
+        kind, nrow, ncol, rows = row[0], row[1], row[2], row[3:8]
+        if row[8] != 0:                                     # a cut block: its first part stands for it
+            continue
+        if kind == 0:
+            R = rows[:nrow]
+            out["tri"] += [(R[u], R[v]) for u in range(nrow) for v in range(u)]
+        elif kind in (1, 4):
+            for r in rows[3:3 + nrow]:
+                for q in rows[:ncol]:
+                    if q < r:
+                        out["rect" if kind == 1 else "rect_diag"].append((r, q))
+                    elif q == r and kind == 4:
+                        out["diag"].append((r, q))
+        elif kind == 2:
+            out["diag"].append((rows[0], rows[0]))
+    return {k: np.array(v, dtype=np.int64).reshape(-1, 2) for k, v in out.items()}
+
+
+def test_config5_n32768_m8192_f32_million_samples_by_block_kind(tb):
+    # the large fp32 shape: a million entries, drawn in equal shares from the tiles of every kind of
+    # block of the plan in force (through tbs_syrk_lower_enumerate) and from the last rows and columns,
+    # each compared with the oracle's extended-precision dot product
+    name, dtype = "syrk_n32768_m8192_f32", np.float32
     _, A, C0, alpha, beta = inputs.make_config(name)
     N, M = A.shape
     dA, dC = _dev(A), _dev(C0)
     tb.tbs_syrk_lower(dA, dC, alpha, beta)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(12345)
-    ii = rng.integers(0, N, size=nsample)
-    jj = (rng.random(nsample) * (ii + 1)).astype(np.int64)
-    # stratify: force samples on the diagonal, in the last (leftover) rows and in the first tile row
-    ii[:200] = jj[:200]
-    ii[200:400] = N - 1 - rng.integers(0, 256, size=200)
-    jj[200:400] = (rng.random(200) * (ii[200:400] + 1)).astype(np.int64)
+    kinds = _tiles_by_block_kind(tb.tbs_syrk_lower_enumerate(tb.TBS_F32, N, M))
+    T = N // 64
+    assert sum(len(v) for v in kinds.values()) == T * (T + 1) // 2
+    rng = np.random.default_rng(2024)
+    ii, jj, used = [], [], []
+    per_kind = -(-1_000_000 // sum(1 for v in kinds.values() if len(v)))
+    for kind, tiles in kinds.items():
+        if len(tiles) == 0:
+            continue
+        used.append(kind)
+        pick = tiles[rng.integers(0, len(tiles), size=per_kind)]
+        i = pick[:, 0] * 64 + rng.integers(0, 64, size=per_kind)
+        j = pick[:, 1] * 64 + rng.integers(0, 64, size=per_kind)
+        if kind == "diag":
+            i, j = np.maximum(i, j), np.minimum(i, j)
+        ii.append(i)
+        jj.append(j)
+    assert "tri" in used and "diag" in used
+    # the edges: the diagonal itself, the last row, the first column
+    d = rng.integers(0, N, size=1000)
+    ii += [d, np.full(1000, N - 1), rng.integers(0, N, size=1000)]
+    jj += [d, rng.integers(0, N, size=1000), np.zeros(1000, dtype=np.int64)]
+    ii, jj = np.concatenate(ii), np.concatenate(jj)
+    assert ii.size >= 1_000_000
+    assert (jj <= ii).all()
     got = dC[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy().astype(np.float64)
     A64 = A.astype(np.float64)
-    C64 = C0.astype(np.float64)
-    ref = oracle.syrk_lower_sample(A64, C64, ii, jj, alpha, beta)
-    den = oracle.syrk_lower_sample(np.abs(A64), np.abs(C64), ii, jj, abs(alpha), abs(beta))
+    ref = oracle.syrk_lower_sample(A64, None, ii, jj, alpha, 0.0)
+    den = oracle.syrk_lower_sample(np.abs(A64), None, ii, jj, abs(alpha), 0.0)
     worst = float((np.abs(got - ref) / np.maximum(den, 1e-300)).max())
     assert worst <= TOL[dtype], f"{name}: componentwise error {worst:.3e}"
-    # property that holds at any size: the strict upper triangle is untouched (check a band of rows)
-    rows = np.unique(np.concatenate([np.arange(0, N, max(N // 64, 1)), [N - 2]]))
+    # a property that holds at any size: nothing above the diagonal is written (C0 is zero there)
+    rows = np.unique(np.concatenate([np.arange(0, N, N // 64), [N - 2]]))
     up = dC[torch.from_numpy(rows).cuda()].cpu().numpy()
     for r, line in zip(rows, up):
-        assert np.array_equal(line[r + 1:], C0[r, r + 1:])
-
-
-def test_config2_n4096_m4096_sampled(tb):
-    _sampled_check(tb, "syrk_n4096_m4096_f64", 20000, np.float64)
-
-
-def test_config3_n16384_m512_sampled(tb):
-    _sampled_check(tb, "syrk_n16384_m512_f64", 20000, np.float64)
-
-
-def test_config5_n32768_m8192_f32_sampled(tb):
-    _sampled_check(tb, "syrk_n32768_m8192_f32", 4000, np.float32)
+        assert not line[r + 1:].any()
 
 
 def test_config2_integer_exact_full_size(tb):
@@ -308,11 +390,13 @@ def test_blocks_cut_along_the_contraction_dimension(tb, N, M):
         torch.cuda.synchronize()
         out = dC.cpu().numpy()
         assert np.array_equal(out[il], Cref[il]) and np.array_equal(out[iu], C0[iu])
-    small = torch.empty(1024, dtype=torch.uint8, device="cuda")     # too small: silently the other plan
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")     # a workspace, but too small: an error
     dC = _dev(C0)
-    tb.tbs_syrk_lower(dA, dC, -1.0, 1.0, workspace=small)
+    with pytest.raises(tb.TbsError) as err:
+        tb.tbs_syrk_lower(dA, dC, -1.0, 1.0, workspace=small)
+    assert err.value.status == tb.TBS_EWORKSPACE
     torch.cuda.synchronize()
-    assert np.array_equal(dC.cpu().numpy()[il], Cref[il])
+    assert np.array_equal(dC.cpu().numpy(), C0)             # nothing was launched
     Ar = inputs.normal_matrix(N, M, seed=53)
     Cg = _run(tb, Ar, C0, 0.5, -1.5)
     Cr, D = _reference(Ar, C0, 0.5, -1.5)
@@ -320,15 +404,18 @@ def test_blocks_cut_along_the_contraction_dimension(tb, N, M):
 
 
 # block shapes pinned through the environment ("levels,rows,cols,base,zone_rows,zone_cols"): among them
-# two-row rectangles in triangular regions, whose blocks straddle the diagonal in three different ways;
-# one size per tuning because the library keeps one plan per size
+# two-row rectangles in triangular regions, whose blocks straddle the diagonal in three different ways
 PINNED = ["0,2,3,0", "1,2,3,0,2,3", "2,2,2,0,2,2", "1,1,3,0,2,1", "1,2,3,0,1,2", "10,2,3,1"]
 
 
 @pytest.mark.parametrize("idx", range(len(PINNED)))
 def test_pinned_block_shapes_bit_exact_and_in_tolerance(tb, idx, monkeypatch):
+    from _plan_util import assert_plan_is_pinned
     monkeypatch.setenv("TBS_PLAN_TUNING", PINNED[idx])
     for N, M in ((1216 + 64 * idx, 48), (1500 + 64 * idx + 7, 80)):     # whole tiles; a ragged last tile
+        # the plan in force for this size is the pinned one (the tuning string is part of the library's
+        # plan-cache key), whatever sizes earlier tests of this process have used
+        assert_plan_is_pinned(tb, tb.TBS_F64, N, M, PINNED[idx])
         A = inputs.small_int_matrix(N, M, seed=30 + idx, dtype=np.float64)
         C0 = inputs.symmetric_uniform(N, seed=40 + idx, dtype=np.float64, int_range=(-9, 9))
         Cg = _run(tb, A, C0, -1.0, 1.0)
@@ -338,6 +425,7 @@ def test_pinned_block_shapes_bit_exact_and_in_tolerance(tb, idx, monkeypatch):
         assert np.array_equal(Cg[il], Cref[il])
         assert np.array_equal(Cg[iu], C0[iu])
     N, M = 1088 + 64 * idx, 64
+    assert_plan_is_pinned(tb, tb.TBS_F64, N, M, PINNED[idx])
     A = inputs.normal_matrix(N, M, 50 + idx, 1.0, np.float64)
     C0 = inputs.symmetric_uniform(N, 60 + idx, dtype=np.float64)
     Cg = _run(tb, A, C0, -1.0, 1.0)
