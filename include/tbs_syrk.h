@@ -88,6 +88,31 @@ tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double a
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * tbs_syrk_lower for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same operation, arguments, plan and results (bit
+ * for bit) as tbs_syrk_lower called with the workspace that tbs_syrk_lower_workspace() asks for, but
+ * the scratch memory (the parts of blocks computed in parts, and the counters of the launch) is an
+ * array at file scope in the library's device code: TBS_NOALLOC_SCRATCH_BYTES of device memory that
+ * every GPU the library runs on holds from the moment the library is loaded until the process ends.
+ * The call allocates and frees nothing on the device, creates no stream or event, and clears the
+ * counters it needs with a small kernel on `hip_stream` (not with a memset).
+ *   Limit: a plan that needs more than TBS_NOALLOC_WORKSPACE_BYTES for its parts (what
+ *   tbs_syrk_lower_workspace() reports: 0 for most sizes, up to 128 MiB for some small N with a long
+ *   contraction; more only for plans pinned through TBS_PLAN_TUNING) is rejected with
+ *   TBS_EWORKSPACE before anything is launched: use tbs_syrk_lower with a workspace of the
+ *   caller's for those.
+ *   All calls on one GPU share the one array, which keeps the last call's contents: calls that may
+ *   run at the same time on one GPU (different streams, no ordering between them) race and give
+ *   wrong results; calls ordered by a stream or by events are fine.
+ * ---------------------------------------------------------------------------------------------- */
+#define TBS_NOALLOC_WORKSPACE_BYTES ((size_t)128 << 20)
+#define TBS_NOALLOC_SCRATCH_BYTES (TBS_NOALLOC_WORKSPACE_BYTES + 4096)
+
+tbs_status tbs_syrk_lower_noalloc(tbs_dtype dtype, int64_t N, int64_t M, double alpha,
+                                  const void* A, int64_t lda, double beta, void* C, int64_t ldc,
+                                  void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
  * The plan the library uses for a given size, for tests and benchmarks (host only).
  * Element counts follow the paper's accounting (Sections 5.1.3, 5.1.4): A elements loaded by
  * every block (k*b*M per triangle block), C elements loaded once.

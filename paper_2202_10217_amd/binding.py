@@ -17,6 +17,7 @@ TBS_F64, TBS_F32 = 0, 1
 TBS_OK, TBS_EINVAL, TBS_EWORKSPACE, TBS_ENOTSPD, TBS_EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tbs_status_string", "tbs_syrk_lower_workspace", "tbs_syrk_lower", "tbs_syrk_lower_square",
+           "tbs_syrk_lower_noalloc",
            "tbs_syrk_lower_query", "tbs_syrk_lower_enumerate", "tbs_potrf_lower_workspace",
            "tbs_potrf_lower")
 
@@ -61,6 +62,8 @@ def load():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [ctypes.c_int, i64, i64, f64, p, i64, f64, p, i64, p, sz, p]
+    lib.tbs_syrk_lower_noalloc.restype = ctypes.c_int
+    lib.tbs_syrk_lower_noalloc.argtypes = [ctypes.c_int, i64, i64, f64, p, i64, f64, p, i64, p]
     lib.tbs_syrk_lower_query.restype = ctypes.c_int
     lib.tbs_syrk_lower_query.argtypes = [ctypes.c_int, i64, i64, i32, ctypes.POINTER(PlanInfo)]
     lib.tbs_syrk_lower_enumerate.restype = ctypes.c_int
@@ -153,6 +156,28 @@ def tbs_syrk_lower(A, C, alpha=1.0, beta=1.0, workspace=None, stream=None):
 def tbs_syrk_lower_square(A, C, alpha=1.0, beta=1.0, workspace=None, stream=None):
     """Same update with rectangular blocks only (the square-block baseline)."""
     return _syrk("tbs_syrk_lower_square", A, C, alpha, beta, workspace, stream)
+
+
+NOALLOC_WORKSPACE_BYTES = 128 << 20
+
+
+def tbs_syrk_lower_noalloc(A, C, alpha=1.0, beta=1.0, stream=None):
+    """tbs_syrk_lower with the library's own file-scope scratch memory: nothing is allocated by the call
+    (nor by this wrapper).  Raises TbsError(TBS_EWORKSPACE) for sizes whose plan needs more than
+    NOALLOC_WORKSPACE_BYTES; calls that overlap on one GPU race."""
+    code = _dtype_code(A)
+    if C.dtype != A.dtype:
+        raise TypeError("A and C must have the same dtype")
+    N, M = A.shape
+    if tuple(C.shape) != (N, N):
+        raise ValueError("C must be N x N")
+    a_ptr, lda = _matrix_args(A, "A")
+    c_ptr, ldc = _matrix_args(C, "C")
+    st = load().tbs_syrk_lower_noalloc(code, N, M, float(alpha), ctypes.c_void_p(a_ptr), lda, float(beta),
+                                       ctypes.c_void_p(c_ptr), ldc, _stream_ptr(stream))
+    if st != TBS_OK:
+        raise TbsError(st, "tbs_syrk_lower_noalloc")
+    return C
 
 
 def tbs_syrk_lower_query(dtype_code, N, M, square=False) -> dict:

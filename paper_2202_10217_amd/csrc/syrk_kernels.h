@@ -24,6 +24,14 @@ struct CounterLease {
 // Calls no allocation routine except for one event per set, created when the set is first handed out.
 hipError_t acquire_counters(hipStream_t stream, CounterLease* out);
 
+// The library's own scratch memory for callers that cannot allocate: a file-scope array in device
+// memory, kStaticCounterBytes for the counters of one launch followed by kStaticWorkspaceBytes for the
+// parts of cut blocks.  *ptr receives its device address on the current device (looked up once per
+// device).  Every call on a device shares the one array.
+constexpr size_t kStaticCounterBytes = 4096;
+constexpr size_t kStaticWorkspaceBytes = (size_t)128 << 20;
+hipError_t static_scratch(unsigned char** ptr);
+
 // C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`.  All pointers are device pointers; sizes
 // have been validated by the caller.  max_workgroups > 0 bounds the launch: a plan with more blocks
 // runs as that many persistent workgroups taking blocks in list order (normally the number of

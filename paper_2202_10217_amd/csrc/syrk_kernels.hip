@@ -900,6 +900,33 @@ hipError_t acquire_counters(hipStream_t stream, CounterLease* out)
     return hipSuccess;
 }
 
+// ---- scratch memory of the entry point that allocates nothing ---------------------------------------
+// Held by every device the library runs on until the process ends.  In host code the name below is
+// only a handle for hipGetSymbolAddress; kernels receive the looked-up address as an argument.
+static_assert(kStaticCounterBytes >= (2 + kSliceCounters) * sizeof(unsigned int), "counters fit");
+static __device__ __align__(256) unsigned char scratch[kStaticCounterBytes + kStaticWorkspaceBytes];
+
+hipError_t static_scratch(unsigned char** out)
+{
+    static std::mutex mu;
+    static unsigned char* per_device[kMaxDevices] = {};
+    *out = nullptr;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {                                 // each device has its own copy at its own address
+        unsigned char* ptr = nullptr;
+        e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        per_device[dev] = ptr;
+    }
+    *out = per_device[dev];
+    return hipSuccess;
+}
+
 hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
                        int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
                        const CounterLease& lease, hipStream_t stream)

@@ -132,6 +132,23 @@ tbs_status check_syrk(tbs_dtype dtype, int64_t N, int64_t M, const void* A, int6
     return TBS_OK;
 }
 
+// Workgroups of a persistent launch that leaves `reserve_units` compute units free (0: launches are
+// not persistent, TBS_SYRK_PERSISTENT=0).
+int persistent_workgroups(int reserve_units)
+{
+    static const bool persistent = [] {
+        const char* v = std::getenv("TBS_SYRK_PERSISTENT");
+        return !(v && v[0] == '0');
+    }();
+    // TBS_SYRK_RESERVE=n keeps n compute units out of every persistent launch (for measurements)
+    static const int env_reserve = [] {
+        const char* v = std::getenv("TBS_SYRK_RESERVE");
+        const long n = v ? std::atol(v) : 0;
+        return (n > 0 && n < 4096) ? (int)n : 0;
+    }();
+    return persistent ? std::max(1, compute_units() - std::max(reserve_units, env_reserve)) : 0;
+}
+
 // The plan a call uses: the one with cut blocks if the caller gave a workspace (which must then hold
 // its parts), else the one without.
 tbs_status plan_for_call(int32_t T, bool square, tbs_dtype dtype, int64_t M, const void* workspace,
@@ -162,17 +179,7 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
     const tbs::Plan* plan = nullptr;
     const tbs_status ps = plan_for_call(T, square, dtype, M, workspace, workspace_bytes, &plan);
     if (ps != TBS_OK) return ps;
-    static const bool persistent = [] {
-        const char* v = std::getenv("TBS_SYRK_PERSISTENT");
-        return !(v && v[0] == '0');
-    }();
-    // TBS_SYRK_RESERVE=n keeps n compute units out of every persistent launch (for measurements)
-    static const int env_reserve = [] {
-        const char* v = std::getenv("TBS_SYRK_RESERVE");
-        const long n = v ? std::atol(v) : 0;
-        return (n > 0 && n < 4096) ? (int)n : 0;
-    }();
-    int wgs = persistent ? std::max(1, compute_units() - std::max(reserve_units, env_reserve)) : 0;
+    int wgs = persistent_workgroups(reserve_units);
     tbs::CounterLease lease;
     if ((wgs > 0 && plan->n_items > wgs) || plan->n_ws_blocks > 0) {
         if (tbs::acquire_counters(stream, &lease) != hipSuccess) return TBS_EHIP;
@@ -480,6 +487,31 @@ tbs_status tbs_syrk_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha, c
     if (st != TBS_OK) return st;
     return syrk_impl(false, dtype, N, M, alpha, A, lda, beta, C, ldc, (hipStream_t)hip_stream, 0, workspace,
                      workspace_bytes);
+}
+
+tbs_status tbs_syrk_lower_noalloc(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A, int64_t lda,
+                                  double beta, void* C, int64_t ldc, void* hip_stream)
+{
+    const tbs_status st = check_syrk(dtype, N, M, A, lda, C, ldc);
+    if (st != TBS_OK) return st;
+    if (N == 0) return TBS_OK;
+    const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    const tbs::Plan* plan = cached_plan(T, false, dtype, M, true);
+    if (!plan) return TBS_EINVAL;
+    if (tbs::syrk_workspace_bytes(dtype == TBS_F32, *plan) > tbs::kStaticWorkspaceBytes) return TBS_EWORKSPACE;
+    unsigned char* base = nullptr;
+    if (tbs::static_scratch(&base) != hipSuccess) return TBS_EHIP;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // the counters start at zero whatever an earlier call (finished, or given up half-way) left there:
+    // cleared by a kernel on the caller's stream (no memset node: the call may be recorded into a graph)
+    tbs::CounterLease lease;
+    lease.ctr = reinterpret_cast<unsigned int*>(base);
+    lease.slice_ctr = lease.ctr + 2;
+    if (tbs::launch_fill_i32(reinterpret_cast<int32_t*>(base), 0, 2 + tbs::kSliceCounters, stream) != hipSuccess)
+        return TBS_EHIP;
+    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc,
+                                          persistent_workgroups(0), base + tbs::kStaticCounterBytes, lease, stream);
+    return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 
 tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A,

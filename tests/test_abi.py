@@ -62,6 +62,25 @@ def test_syrk_argument_checks(lib, entry):
     assert _syrk(lib, entry, 0, 0, 8, None, 8, None, 1) == tb.TBS_OK          # N = 0: nothing to do
 
 
+def test_noalloc_argument_checks(lib, monkeypatch):
+    fake = ctypes.c_void_p(0x1000)                            # never dereferenced: checks come first
+    f = lib.tbs_syrk_lower_noalloc
+    assert f(7, 4, 4, 1.0, fake, 4, 1.0, fake, 4, None) == tb.TBS_EINVAL      # dtype
+    assert f(0, -1, 4, 1.0, fake, 4, 1.0, fake, 4, None) == tb.TBS_EINVAL     # N < 0
+    assert f(0, 4, 8, 1.0, fake, 7, 1.0, fake, 4, None) == tb.TBS_EINVAL      # lda < M
+    assert f(0, 4, 8, 1.0, fake, 8, 1.0, fake, 3, None) == tb.TBS_EINVAL      # ldc < N
+    assert f(0, 4, 8, 1.0, None, 8, 1.0, fake, 4, None) == tb.TBS_EINVAL      # A NULL
+    assert f(0, 0, 8, 1.0, None, 8, 1.0, None, 1, None) == tb.TBS_OK          # N = 0: nothing to do
+    # a plan whose parts do not fit the library's scratch array is refused before anything is launched
+    monkeypatch.setenv("TBS_PLAN_TUNING", "1,2,3,0,2,3,16,1,0,1")
+    assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, 4096, 4096) > tb.NOALLOC_WORKSPACE_BYTES
+    assert f(0, 4096, 4096, 1.0, fake, 4096, 1.0, fake, 4096, None) == tb.TBS_EWORKSPACE
+    # the header's constant is the binding's
+    text = open(os.path.join(ROOT, "include", "tbs_syrk.h")).read()
+    assert re.search(r"#define TBS_NOALLOC_WORKSPACE_BYTES \(\(size_t\)128 << 20\)", text)
+    assert tb.NOALLOC_WORKSPACE_BYTES == 128 << 20
+
+
 def test_workspace_queries(lib):
     big = tb.tbs_syrk_lower_query(tb.TBS_F64, 32768, 512)
     assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, 32768, 512) == 0 == big["workspace_bytes"]   # many blocks per unit

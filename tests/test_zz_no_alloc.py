@@ -1,0 +1,98 @@
+"""The entry point that allocates nothing (tbs_syrk_lower_noalloc) against tbs_syrk_lower, through the
+C ABI: same plan and same order of the sums, so the results must agree bit for bit (which is inside the
+stated tolerance, 1e-13 / 2e-5 componentwise, a fortiori).  Calls follow each other on one stream, the
+later ones with smaller inputs: the library's one scratch array still holds the earlier call's parts
+and counters then."""
+import numpy as np
+import pytest
+
+from paper_2202_10217_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tb():
+    from paper_2202_10217_amd import binding
+    binding.load()
+    return binding
+
+
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def _both(tb, A, C0, alpha, beta):
+    """(result of tbs_syrk_lower with its workspace, device tensors for the no-alloc call)."""
+    dA, dC = _dev(A), _dev(C0)
+    code = tb.TBS_F64 if A.dtype == np.float64 else tb.TBS_F32
+    need = tb.tbs_syrk_lower_workspace(code, *A.shape)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else False
+    tb.tbs_syrk_lower(dA, dC, alpha, beta, workspace=ws)
+    torch.cuda.synchronize()
+    return dC.cpu().numpy(), dA, _dev(C0)
+
+
+def test_two_calls_in_a_row_the_second_smaller_match_the_allocating_entry_point(tb):
+    # sizes: the benchmark shape (blocks cut in parts, persistent launch: both kinds of counters and
+    # 54 MiB of parts in the scratch array), then a smaller one with cut blocks, then one whose plan has
+    # none, then the first again; random data, alpha and beta general
+    shapes = [(4096, 4096, np.float64), (1100, 3000, np.float64), (700, 100, np.float64), (2048, 4096, np.float32),
+              (4096, 4096, np.float64)]
+    assert tb.tbs_syrk_lower_query(tb.TBS_F64, 4096, 4096)["n_sliced_blocks"] > 0
+    assert tb.tbs_syrk_lower_query(tb.TBS_F64, 1100, 3000)["n_sliced_blocks"] > 0
+    cases = []
+    for n, (N, M, dtype) in enumerate(shapes):
+        A = inputs.normal_matrix(N, M, seed=70 + n, scale=1.0 / np.sqrt(M), dtype=dtype)
+        C0 = inputs.symmetric_uniform(N, seed=80 + n, dtype=dtype)
+        C0[np.triu_indices(N, 1)] = np.nan
+        want, dA, dC = _both(tb, A, C0, -0.5, 1.25)
+        cases.append((want, dA, dC, C0))
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    for want, dA, dC, C0 in cases:                           # back to back on the current stream
+        tb.tbs_syrk_lower_noalloc(dA, dC, -0.5, 1.25)
+    assert torch.cuda.memory_allocated() == before
+    torch.cuda.synchronize()
+    for n, (want, dA, dC, C0) in enumerate(cases):
+        got = dC.cpu().numpy()
+        assert np.array_equal(got, want, equal_nan=True), shapes[n]
+
+
+def test_integer_data_against_the_oracle_and_repeat(tb):
+    # the same entry point against the oracle itself (integer data: bit for bit), twice in a row
+    import oracle
+    N, M = 2048, 2080
+    A = inputs.small_int_matrix(N, M, seed=91)
+    C0 = inputs.symmetric_uniform(N, seed=92, int_range=(-3, 3))
+    Cref = C0.copy()
+    oracle.syrk_lower(A, Cref, -1.0, 1.0)
+    il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+    dA = _dev(A)
+    for _ in range(2):
+        dC = _dev(C0)
+        tb.tbs_syrk_lower_noalloc(dA, dC, -1.0, 1.0)
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy()
+        assert np.array_equal(out[il], Cref[il]) and np.array_equal(out[iu], C0[iu])
+
+
+def test_sizes_beyond_the_scratch_array_are_rejected(tb, monkeypatch):
+    # a plan that needs more room for its parts than the array has (the library's own choices stay
+    # within it; a pinned plan with every triangle block cut in 16 does not): a clear error, nothing
+    # launched
+    N, M = 4096, 4096
+    assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, N, M) <= tb.NOALLOC_WORKSPACE_BYTES
+    monkeypatch.setenv("TBS_PLAN_TUNING", "1,2,3,0,2,3,16,1,0,1")
+    assert tb.tbs_syrk_lower_workspace(tb.TBS_F64, N, M) > tb.NOALLOC_WORKSPACE_BYTES
+    dA = torch.zeros((N, M), dtype=torch.float64, device="cuda")
+    dC = torch.ones((N, N), dtype=torch.float64, device="cuda")
+    with pytest.raises(tb.TbsError) as err:
+        tb.tbs_syrk_lower_noalloc(dA, dC, 1.0, 0.0)
+    assert err.value.status == tb.TBS_EWORKSPACE
+    torch.cuda.synchronize()
+    assert bool((dC == 1.0).all())
+    # empty problems and bad arguments behave as in the other entry points
+    tb.tbs_syrk_lower_noalloc(torch.empty((0, 5), dtype=torch.float64, device="cuda"),
+                              torch.empty((0, 0), dtype=torch.float64, device="cuda"))
