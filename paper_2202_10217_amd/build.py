@@ -21,9 +21,11 @@ def generate_loops() -> str:
     return mod.main()
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, incremental: bool = False) -> str:
     """Compiles the translation units in parallel (the SYRK kernels are compiled once per element type
-    and kernel family: each takes a minute or two) and links them."""
+    and kernel family: each takes a minute or two) and links them.  incremental=True (a developer's
+    shortcut, `--incremental` on the command line) keeps an object file that is newer than every source
+    and header; the default compiles everything."""
     from concurrent.futures import ThreadPoolExecutor
     os.makedirs(OUT_DIR, exist_ok=True)
     obj_dir = os.path.join(OUT_DIR, "obj")
@@ -45,10 +47,16 @@ def build(verbose: bool = False) -> str:
              ("tbs_planner", os.path.join(CSRC, "tbs_planner.cpp"), []),
              ("tbs_api", os.path.join(CSRC, "tbs_api.cpp"), [])]
     noise = "is not a recognized feature for this target"
+    deps = [os.path.join(d, f) for d in (CSRC, os.path.join(ROOT, "include")) for f in os.listdir(d)
+            if f.endswith((".h", ".inc", ".hip", ".cpp"))]
 
     def compile_unit(unit):
         name, src, defs = unit
         obj = os.path.join(obj_dir, name + ".o")
+        if incremental and os.path.exists(obj):
+            own = [src] + [f for f in deps if f.endswith((".h", ".inc"))]
+            if os.path.getmtime(obj) >= max(os.path.getmtime(f) for f in own):
+                return obj, ""
         res = subprocess.run(common + defs + ["-c", src, "-o", obj], capture_output=True, text=True)
         err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
         if res.returncode != 0:
@@ -70,4 +78,4 @@ def build(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     import sys
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, incremental="--incremental" in sys.argv))

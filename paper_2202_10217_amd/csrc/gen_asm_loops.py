@@ -235,8 +235,10 @@ def main():
                    f"    static __device__ __forceinline__ void run(Cfg<{ty}>::acc_t (&acc)[6][4], "
                    f"const AsmLoopArgs& g, const uint32_t (&go)[10]) {{ {name}(acc, g, go); }}\n}};\n")
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "syrk_asm_loops.inc")
-    with open(path, "w") as f:
-        f.write("".join(out))
+    text = "".join(out)
+    if not (os.path.exists(path) and open(path).read() == text):   # untouched when nothing changed
+        with open(path, "w") as f:
+            f.write(text)
     return path
 
 
