@@ -36,6 +36,10 @@ def _load():
         fn.argtypes = [i64, i64, f64, p, i64, f64, p, i64]
     lib.oracle_syrk_lower_f64_ext_sample.restype = None
     lib.oracle_syrk_lower_f64_ext_sample.argtypes = [i64, f64, p, i64, f64, p, i64, i64, p, p, p]
+    lib.oracle_syr2k_lower_f64.restype = None
+    lib.oracle_syr2k_lower_f64.argtypes = [i64, i64, f64, p, i64, p, i64, f64, p, i64, ctypes.c_int]
+    lib.oracle_gram_lower_f64.restype = None
+    lib.oracle_gram_lower_f64.argtypes = [i64, i64, f64, p, i64, f64, p, i64, ctypes.c_int]
     lib.oracle_potrf_lower_f64.restype = i64
     lib.oracle_potrf_lower_f64.argtypes = [i64, p, i64]
     lib.oracle_llt_residual_sq.restype = f64
@@ -107,6 +111,37 @@ def syrk_lower_sample(A, C, ii, jj, alpha=1.0, beta=1.0):
                                              cptr, ldc, ii.size, ii.ctypes.data, jj.ctypes.data,
                                              out.ctypes.data)
     return out
+
+
+def syr2k_lower(A, B, C, alpha=1.0, beta=1.0, extended=True):
+    """C[i,j] <- beta*C[i,j] + alpha*sum_k (A[i,k]B[j,k] + B[i,k]A[j,k]) for j<=i, in place (the
+    textbook SYR2K; one of the "kernels that use an input several times" of the paper's conclusion)."""
+    A = _as_f64_matrix(A, "A")
+    B = _as_f64_matrix(B, "B")
+    C = _as_f64_matrix(C, "C")
+    N, M = A.shape
+    if B.shape != (N, M) or C.shape != (N, N):
+        raise ValueError("B must be N x M and C N x N")
+    if not C.flags.writeable:
+        raise ValueError("C must be writeable")
+    _load().oracle_syr2k_lower_f64(N, M, float(alpha), A.ctypes.data, _ld(A), B.ctypes.data, _ld(B),
+                                   float(beta), C.ctypes.data, _ld(C), 1 if extended else 0)
+    return C
+
+
+def gram_lower(A, C, alpha=1.0, beta=1.0, extended=True):
+    """C[i,j] <- beta*C[i,j] + alpha*sum_k A[k,i]A[k,j] for j<=i (C is M x M for an N x M matrix A),
+    in place: the Gram matrix A^T A, i.e. Algorithm 1 applied to the transpose."""
+    A = _as_f64_matrix(A, "A")
+    C = _as_f64_matrix(C, "C")
+    N, M = A.shape
+    if C.shape != (M, M):
+        raise ValueError("C must be M x M")
+    if not C.flags.writeable:
+        raise ValueError("C must be writeable")
+    _load().oracle_gram_lower_f64(N, M, float(alpha), A.ctypes.data, _ld(A), float(beta), C.ctypes.data,
+                                  _ld(C), 1 if extended else 0)
+    return C
 
 
 def potrf_lower(S):

@@ -160,3 +160,78 @@ double oracle_llt_residual_sq(int64_t N, const double *L, int64_t ldl,
     *norm2 = (double)nrm;
     return (double)acc;
 }
+
+/* ---------------------------------------------------------------------------
+ * Two more kernels that use an input twice (the paper's conclusion names the
+ * extension to "other kernels which use the same input several times" as
+ * future work; it defines neither, so these are the textbook definitions,
+ * written as the same kind of triple loop as Algorithm 1).
+ *
+ * SYR2K, lower triangle:
+ *   C[i][j] <- beta*C[i][j] + alpha * sum_k (A[i][k]*B[j][k] + B[i][k]*A[j][k]),  j <= i.
+ * Gram matrix, lower triangle (A is N x M, C is M x M):
+ *   C[i][j] <- beta*C[i][j] + alpha * sum_k A[k][i]*A[k][j],  j <= i.
+ * `ext` != 0 carries the sums in long double (the parity yardstick), 0 is the
+ * plain double loop.  beta == 0: C is write-only.  Entries above the diagonal
+ * are neither read nor written.
+ * ------------------------------------------------------------------------- */
+void oracle_syr2k_lower_f64(int64_t N, int64_t M, double alpha,
+                            const double *A, int64_t lda,
+                            const double *B, int64_t ldb,
+                            double beta, double *C, int64_t ldc, int ext)
+{
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < N; ++i) {
+        for (int64_t j = 0; j <= i; ++j) {
+            if (ext) {
+                long double s = 0.0L;
+                for (int64_t k = 0; k < M; ++k) {
+                    s += (long double)A[i * lda + k] * (long double)B[j * ldb + k];
+                    s += (long double)B[i * ldb + k] * (long double)A[j * lda + k];
+                }
+                long double r = (long double)alpha * s;
+                if (beta != 0.0)
+                    r += (long double)beta * (long double)C[i * ldc + j];
+                C[i * ldc + j] = (double)r;
+            } else {
+                double s = 0.0;
+                for (int64_t k = 0; k < M; ++k) {
+                    s += A[i * lda + k] * B[j * ldb + k];
+                    s += B[i * ldb + k] * A[j * lda + k];
+                }
+                if (beta == 0.0)
+                    C[i * ldc + j] = alpha * s;
+                else
+                    C[i * ldc + j] = beta * C[i * ldc + j] + alpha * s;
+            }
+        }
+    }
+}
+
+void oracle_gram_lower_f64(int64_t N, int64_t M, double alpha,
+                           const double *A, int64_t lda,
+                           double beta, double *C, int64_t ldc, int ext)
+{
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j <= i; ++j) {
+            if (ext) {
+                long double s = 0.0L;
+                for (int64_t k = 0; k < N; ++k)
+                    s += (long double)A[k * lda + i] * (long double)A[k * lda + j];
+                long double r = (long double)alpha * s;
+                if (beta != 0.0)
+                    r += (long double)beta * (long double)C[i * ldc + j];
+                C[i * ldc + j] = (double)r;
+            } else {
+                double s = 0.0;
+                for (int64_t k = 0; k < N; ++k)
+                    s += A[k * lda + i] * A[k * lda + j];
+                if (beta == 0.0)
+                    C[i * ldc + j] = alpha * s;
+                else
+                    C[i * ldc + j] = beta * C[i * ldc + j] + alpha * s;
+            }
+        }
+    }
+}
