@@ -88,6 +88,39 @@ tbs_status tbs_syrk_lower_square(tbs_dtype dtype, int64_t N, int64_t M, double a
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Two more kernels that use an input twice (the extension the paper's conclusion points to), built
+ * from the same blocks and main loops.
+ *
+ * SYR2K, lower triangle:
+ *     C[i][j] <- beta * C[i][j] + alpha * sum_{k<M} (A[i][k] * B[j][k] + B[i][k] * A[j][k]),  j <= i.
+ *   A, B  device, N x M, lda, ldb >= max(M,1), never written; C device, N x N, ldc >= max(N,1).
+ *   Schedule: rectangular blocks of up to 2 x 3 tiles (the square-block scheme of Section 5); a
+ *   block streams (rows of A, rows of B) and then (rows of B, rows of A) into one set of
+ *   accumulators and touches its part of C once.  A triangle block would need the panels of both
+ *   matrices for all of its k tile rows at once, twice what a compute unit's LDS and registers
+ *   hold beside k(k-1)/2 tiles, so the triangle-block schedule is not used here.
+ *
+ * Gram matrix, lower triangle (SYRK of the transpose, A stored as it is):
+ *     C[i][j] <- beta * C[i][j] + alpha * sum_{k<N} A[k][i] * A[k][j],  0 <= j <= i < M.
+ *   A  device, N x M row-major, lda >= max(M,1), never written; C device, M x M, ldc >= max(M,1).
+ *   Schedule: the Triangle Block Scheme of tbs_syrk_lower on the M/b column panels of A (a panel's
+ *   "row" is a column of A; a staged chunk is 16 or 32 memory rows of 64 columns); workspace as for
+ *   tbs_syrk_lower, sized by tbs_gram_lower_workspace().  When M is no multiple of 2 (fp64) or 4
+ *   (fp32) every block takes the slower, fully checked loop.
+ * Both: N, M >= 0; an empty contraction scales the lower triangle by beta; beta == 0 means C is
+ * write-only; nothing above the diagonal is read or written; asynchronous on hip_stream.
+ * ---------------------------------------------------------------------------------------------- */
+tbs_status tbs_syr2k_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha,
+                           const void* A, int64_t lda, const void* B, int64_t ldb,
+                           double beta, void* C, int64_t ldc, void* hip_stream);
+
+tbs_status tbs_gram_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_t* bytes);
+
+tbs_status tbs_gram_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha,
+                          const void* A, int64_t lda, double beta, void* C, int64_t ldc,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
  * tbs_syrk_lower for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same operation, arguments, plan and results (bit
  * for bit) as tbs_syrk_lower called with the workspace that tbs_syrk_lower_workspace() asks for, but

@@ -17,7 +17,7 @@ TBS_F64, TBS_F32 = 0, 1
 TBS_OK, TBS_EINVAL, TBS_EWORKSPACE, TBS_ENOTSPD, TBS_EHIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tbs_status_string", "tbs_syrk_lower_workspace", "tbs_syrk_lower", "tbs_syrk_lower_square",
-           "tbs_syrk_lower_noalloc",
+           "tbs_syrk_lower_noalloc", "tbs_syr2k_lower", "tbs_gram_lower", "tbs_gram_lower_workspace",
            "tbs_syrk_lower_query", "tbs_syrk_lower_enumerate", "tbs_potrf_lower_workspace",
            "tbs_potrf_lower")
 
@@ -64,6 +64,12 @@ def load():
         fn.argtypes = [ctypes.c_int, i64, i64, f64, p, i64, f64, p, i64, p, sz, p]
     lib.tbs_syrk_lower_noalloc.restype = ctypes.c_int
     lib.tbs_syrk_lower_noalloc.argtypes = [ctypes.c_int, i64, i64, f64, p, i64, f64, p, i64, p]
+    lib.tbs_syr2k_lower.restype = ctypes.c_int
+    lib.tbs_syr2k_lower.argtypes = [ctypes.c_int, i64, i64, f64, p, i64, p, i64, f64, p, i64, p]
+    lib.tbs_gram_lower.restype = ctypes.c_int
+    lib.tbs_gram_lower.argtypes = [ctypes.c_int, i64, i64, f64, p, i64, f64, p, i64, p, sz, p]
+    lib.tbs_gram_lower_workspace.restype = ctypes.c_int
+    lib.tbs_gram_lower_workspace.argtypes = [ctypes.c_int, i64, i64, ctypes.POINTER(sz)]
     lib.tbs_syrk_lower_query.restype = ctypes.c_int
     lib.tbs_syrk_lower_query.argtypes = [ctypes.c_int, i64, i64, i32, ctypes.POINTER(PlanInfo)]
     lib.tbs_syrk_lower_enumerate.restype = ctypes.c_int
@@ -177,6 +183,60 @@ def tbs_syrk_lower_noalloc(A, C, alpha=1.0, beta=1.0, stream=None):
                                        ctypes.c_void_p(c_ptr), ldc, _stream_ptr(stream))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_noalloc")
+    return C
+
+
+def tbs_syr2k_lower(A, B, C, alpha=1.0, beta=1.0, stream=None):
+    """C[lower] <- beta*C + alpha*(A B^T + B A^T), in place, asynchronous."""
+    code = _dtype_code(A)
+    if C.dtype != A.dtype or B.dtype != A.dtype:
+        raise TypeError("A, B and C must have the same dtype")
+    N, M = A.shape
+    if tuple(B.shape) != (N, M) or tuple(C.shape) != (N, N):
+        raise ValueError("B must be N x M and C N x N")
+    a_ptr, lda = _matrix_args(A, "A")
+    b_ptr, ldb = _matrix_args(B, "B")
+    c_ptr, ldc = _matrix_args(C, "C")
+    st = load().tbs_syr2k_lower(code, N, M, float(alpha), ctypes.c_void_p(a_ptr), lda, ctypes.c_void_p(b_ptr), ldb,
+                                float(beta), ctypes.c_void_p(c_ptr), ldc, _stream_ptr(stream))
+    if st != TBS_OK:
+        raise TbsError(st, "tbs_syr2k_lower")
+    return C
+
+
+def tbs_gram_lower_workspace(dtype_code, N, M) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().tbs_gram_lower_workspace(dtype_code, N, M, ctypes.byref(out))
+    if st != TBS_OK:
+        raise TbsError(st, "tbs_gram_lower_workspace")
+    return int(out.value)
+
+
+def tbs_gram_lower(A, C, alpha=1.0, beta=1.0, workspace=None, stream=None):
+    """C[lower] (M x M) <- beta*C + alpha*A^T A for a row-major N x M matrix A, in place, asynchronous.
+    workspace as for tbs_syrk_lower (None: allocated here when the plan needs one; False: none)."""
+    code = _dtype_code(A)
+    if C.dtype != A.dtype:
+        raise TypeError("A and C must have the same dtype")
+    N, M = A.shape
+    if tuple(C.shape) != (M, M):
+        raise ValueError("C must be M x M")
+    a_ptr, lda = _matrix_args(A, "A")
+    c_ptr, ldc = _matrix_args(C, "C")
+    if workspace is None:
+        import torch
+        need = tbs_gram_lower_workspace(code, N, M)
+        if need > 0:
+            with torch.cuda.stream(stream if stream is not None else torch.cuda.current_stream()):
+                workspace = torch.empty(need, dtype=torch.uint8, device=A.device)
+    elif workspace is False:
+        workspace = None
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) \
+        if workspace is not None else (None, 0)
+    st = load().tbs_gram_lower(code, N, M, float(alpha), ctypes.c_void_p(a_ptr), lda, float(beta),
+                               ctypes.c_void_p(c_ptr), ldc, ctypes.c_void_p(ws_ptr), ws_bytes, _stream_ptr(stream))
+    if st != TBS_OK:
+        raise TbsError(st, "tbs_gram_lower")
     return C
 
 

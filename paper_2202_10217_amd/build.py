@@ -40,6 +40,8 @@ def build(verbose: bool = False, incremental: bool = False) -> str:
     syrk = os.path.join(CSRC, "syrk_kernels.hip")
     units = [("syrk_f64", syrk, ["-DTBS_UNIT_SYRK", "-DTBS_UNIT_TYPE=double"]),
              ("syrk_f32", syrk, ["-DTBS_UNIT_SYRK", "-DTBS_UNIT_TYPE=float"]),
+             ("syr2k_f64", syrk, ["-DTBS_UNIT_SYR2K", "-DTBS_UNIT_TYPE=double"]),
+             ("syr2k_f32", syrk, ["-DTBS_UNIT_SYR2K", "-DTBS_UNIT_TYPE=float"]),
              ("gemm_f64", syrk, ["-DTBS_UNIT_GEMM", "-DTBS_UNIT_TYPE=double"]),
              ("gemm_f32", syrk, ["-DTBS_UNIT_GEMM", "-DTBS_UNIT_TYPE=float"]),
              ("syrk_dispatch", syrk, ["-DTBS_UNIT_DISPATCH"]),
@@ -54,7 +56,9 @@ def build(verbose: bool = False, incremental: bool = False) -> str:
         name, src, defs = unit
         obj = os.path.join(obj_dir, name + ".o")
         if incremental and os.path.exists(obj):
-            own = [src] + [f for f in deps if f.endswith((".h", ".inc"))]
+            # (only tbs_api.cpp includes the public header)
+            own = [src] + [f for f in deps if f.endswith((".h", ".inc")) and
+                           (name == "tbs_api" or os.path.dirname(f) == CSRC)]
             if os.path.getmtime(obj) >= max(os.path.getmtime(f) for f in own):
                 return obj, ""
         res = subprocess.run(common + defs + ["-c", src, "-o", obj], capture_output=True, text=True)

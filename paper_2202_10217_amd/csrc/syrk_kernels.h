@@ -32,16 +32,33 @@ constexpr size_t kStaticCounterBytes = 4096;
 constexpr size_t kStaticWorkspaceBytes = (size_t)128 << 20;
 hipError_t static_scratch(unsigned char** ptr);
 
-// C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`.  All pointers are device pointers; sizes
-// have been validated by the caller.  max_workgroups > 0 bounds the launch: a plan with more blocks
+// An operand matrix as the kernels address it: element (row, k) of its panels is p[row * rs + k * ks]
+// (device pointer).  A row-major N x M matrix with the contraction along its rows: rs = leading
+// dimension, ks = 1.  The Gram form A^T A of a row-major matrix (panel row = column of A, contraction
+// down its rows): rs = 1, ks = leading dimension.
+struct OperandDesc {
+    const void* p;
+    int64_t rs, ks;
+};
+
+// C[lower] <- beta*C + alpha*A*A^T for the blocks of `plan`; C is N x N, the contraction has length M.
+// All pointers are device pointers; sizes have been validated by the caller.  max_workgroups > 0
+// bounds the launch: a plan with more blocks
 // runs as that many persistent workgroups taking blocks in list order (normally the number of
 // compute units; fewer leaves units free for kernels of other streams); <= 0: one workgroup per block.
 // The persistent form and plans with cut blocks need a lease from acquire_counters (same stream).
 // A plan with sliced blocks needs `workspace`: device memory of syrk_workspace_bytes(), aligned to the
 // element size, contents arbitrary; it is only written and read by this launch.
-hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
+hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
+                       double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
                        const CounterLease& lease, hipStream_t stream);
+
+// C[lower] <- beta*C + alpha*(A*B^T + B*A^T): every block runs over the contraction dimension twice,
+// (A rows, B columns) then (B rows, A columns), into the same accumulators.  The plan must consist of
+// rectangular blocks (no triangle blocks, no cut blocks); hipErrorInvalidValue otherwise.
+hipError_t launch_syr2k(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
+                        const OperandDesc& b, double beta, void* C, int64_t ldc, int max_workgroups,
+                        const CounterLease& lease, hipStream_t stream);
 size_t syrk_workspace_bytes(bool f32, const Plan& plan);
 
 // C (m x n) <- beta*C + alpha * R (m x K) * Q (n x K)^T, all row-major device matrices that do not

@@ -115,13 +115,25 @@ template <class Shape> constexpr uint32_t panels_of(uint32_t slots)
 }
 
 // ---- operands of one launch --------------------------------------------------------------------
-// C[rows, cols] <- beta*C + alpha * R[rows, :] * Q[cols, :]^T.  SYRK has R == Q == A and updates
-// only tiles strictly below the diagonal; the general product (used by the Cholesky driver for its
-// triangular solves) has two different matrices and updates every tile.
+// One operand matrix: element (row, k) of its panels is p[row * rs + k * ks].  Row panels (SYRK, SYR2K,
+// the products of the Cholesky driver; the matrix is stored row-major with the contraction index along
+// a row): rs = leading dimension, ks = 1.  Column panels (the Gram form A^T A: a "row" of the operand
+// is a column of the stored matrix): rs = 1, ks = leading dimension.
 template <typename T>
+struct Side {
+    const T* p;
+    int64_t rs, ks;
+};
+
+// C[rows, cols] <- beta*C + alpha * sum over the passes of R_pass[rows, :] * Q_pass[cols, :]^T.  SYRK
+// has one pass with R == Q == A and updates only tiles strictly below the diagonal (and the lower
+// part of diagonal tiles); the general product (used by the Cholesky driver for its triangular solves)
+// has two different matrices and updates every tile; SYR2K has two passes, (A, B) and (B, A).
+template <typename T, int NPASS_ = 1>
 struct Mats {
-    const T* R;  int64_t ldr;  int nr;      // row-side matrix, nr rows
-    const T* Q;  int64_t ldq;  int nq;      // column-side matrix, nq rows
+    static constexpr int NPASS = NPASS_;
+    Side<T> R[NPASS_];  int nr;             // row-side operand of every pass, nr panel rows
+    Side<T> Q[NPASS_];  int nq;             // column-side operand, nq panel rows
     T* C;        int64_t ldc;
     int M;                                  // contraction length
     T alpha, beta;
@@ -143,15 +155,16 @@ struct Stager {
     static constexpr int KC = Cfg<T>::KC, LDK = Cfg<T>::LDK, VEC = Cfg<T>::VEC;
     u32x4 reg[2 * NP];
     const T* base[NP];                     // matrix of each panel (wavefront-uniform)
-    int64_t ld[NP];
+    int64_t rs[NP], ks[NP];                // its strides between panel rows / along the contraction
     int64_t off[NP];                       // element offset of the thread's first piece in chunk 0
     uint32_t valid;                        // bit 2p+h: piece h of panel p exists (inside the matrix)
 
     static constexpr bool on(int p) { return (PANELS >> p) & 1u; }
 
     // prow[p]: tile row of panel p (-1: absent) in matrix base_[p] with nrows[p] rows.
-    __device__ __forceinline__ void init(const T* const (&base_)[NP], const int64_t (&ld_)[NP],
-                                         const int (&nrows)[NP], const int (&prow)[NP], int tid)
+    __device__ __forceinline__ void init(const T* const (&base_)[NP], const int64_t (&rs_)[NP],
+                                         const int64_t (&ks_)[NP], const int (&nrows)[NP],
+                                         const int (&prow)[NP], int tid)
     {
         const int v = tid & 7, r = tid >> 3;
         valid = 0;
@@ -159,16 +172,18 @@ struct Stager {
         for (int p = 0; p < NP; ++p) {
             if (!on(p)) continue;
             base[p] = base_[p];
-            ld[p] = ld_[p];
+            rs[p] = rs_[p];
+            ks[p] = ks_[p];
             const int grow = prow[p] * kTile + r;
-            off[p] = (int64_t)grow * ld_[p] + v * VEC;
+            off[p] = (int64_t)grow * rs_[p] + (int64_t)(v * VEC) * ks_[p];
             if (prow[p] >= 0 && grow < nrows[p]) valid |= 1u << (2 * p);
             if (prow[p] >= 0 && grow + 32 < nrows[p]) valid |= 2u << (2 * p);
         }
     }
 
-    // General case.  whole: the chunk lies inside [0, M) and 16-byte loads are legal; otherwise
-    // elements are fetched one by one and those beyond M read as zero.  Missing rows read as zero.
+    // General case.  whole: the chunk lies inside [0, M), the contraction index runs along memory
+    // and 16-byte loads are legal; otherwise elements are fetched one by one and those beyond M read
+    // as zero.  Missing rows read as zero.
     __device__ __forceinline__ void load_checked(int M, int k0, bool whole, int tid)
     {
         const int v = tid & 7;
@@ -180,13 +195,13 @@ struct Stager {
                 union { u32x4 q4; T e[VEC]; } tmp;
                 tmp.q4 = u32x4{0u, 0u, 0u, 0u};
                 if ((valid >> (2 * p + h)) & 1u) {
-                    const T* src = base[p] + off[p] + (int64_t)h * 32 * ld[p] + k0;
+                    const T* src = base[p] + off[p] + (int64_t)h * 32 * rs[p] + (int64_t)k0 * ks[p];
                     if (whole) {
                         tmp.q4 = *reinterpret_cast<const u32x4*>(src);
                     } else {
 #pragma unroll
                         for (int e = 0; e < VEC; ++e)
-                            if (k0 + v * VEC + e < M) tmp.e[e] = src[e];
+                            if (k0 + v * VEC + e < M) tmp.e[e] = src[(int64_t)e * ks[p]];
                     }
                 }
                 reg[p * 2 + h] = tmp.q4;
@@ -254,6 +269,17 @@ __device__ __forceinline__ void mfma_step(const Operands<T, Shape, SLOTS>& op,
 }
 
 
+// A value that is the same in every lane, moved to a scalar register (the assembly loops take their
+// pointers and counts as scalar operands; the compiler cannot always see that a value is uniform).
+__device__ __forceinline__ uint32_t to_scalar(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+template <typename P>
+__device__ __forceinline__ const P* to_scalar(const P* p)
+{
+    const uint64_t u = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = to_scalar((uint32_t)u), hi = to_scalar((uint32_t)(u >> 32));
+    return (const P*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
 // ---- the main loop in assembly (generated) -----------------------------------------------------
 struct AsmLoopArgs {
     uint32_t ada[8];        // LDS byte address of the lane's row-side operand piece for k-step j
@@ -271,8 +297,8 @@ struct TileStrip {
     T v[4][4];
     // CHECK: rows / columns beyond the matrix are skipped (ragged last tile)
     // diag: the strip belongs to a diagonal tile; elements above the diagonal are not touched
-    template <bool CHECK>
-    __device__ __forceinline__ void load(const Mats<T>& m, int row0, int col, int lane, bool diag)
+    template <bool CHECK, class MatsT>
+    __device__ __forceinline__ void load(const MatsT& m, int row0, int col, int lane, bool diag)
     {
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb)
@@ -286,8 +312,8 @@ struct TileStrip {
 };
 
 // Writes C <- beta*old + alpha*acc for one tile strip (beta == 0: old is not used).
-template <typename T, bool CHECK>
-__device__ __forceinline__ void store_strip(const Mats<T>& m, int row0, int col, int lane,
+template <typename T, bool CHECK, class MatsT>
+__device__ __forceinline__ void store_strip(const MatsT& m, int row0, int col, int lane,
                                             const typename Cfg<T>::acc_t (&acc)[4], const TileStrip<T>& old,
                                             bool diag)
 {
@@ -331,8 +357,8 @@ struct SliceCtx {
 //   last whole chunk go through the checked loop afterwards.
 //   !FAST: anything else (ragged edges, odd leading dimensions, unusual slot sets); same schedule
 //   with every access checked.
-template <typename T, class Shape, uint32_t SLOTS, bool FAST, bool CAN_SLICE>
-__device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
+template <typename T, class Shape, uint32_t SLOTS, bool FAST, bool CAN_SLICE, class MatsT>
+__device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Shape::NP], uint32_t pmask,
                                            uint32_t dmask, T* lds, const SliceCtx<T>& sc, bool ragged)
 {
     constexpr int NP = Shape::NP;
@@ -347,15 +373,8 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     int nrows[NP];
-    const T* base[NP];
-    int64_t ld[NP];
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const bool col_side = Shape::col_side(p);
-        base[p] = col_side ? m.Q : m.R;
-        ld[p] = col_side ? m.ldq : m.ldr;
-        nrows[p] = col_side ? m.nq : m.nr;
-    }
+    for (int p = 0; p < NP; ++p) nrows[p] = Shape::col_side(p) ? m.nq : m.nr;
 
     acc_t acc[Shape::NSLOT][4];
 #pragma unroll
@@ -364,7 +383,19 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
         for (int rb = 0; rb < 4; ++rb) acc[s][rb] = acc_t{0, 0, 0, 0};
 
     const int M = m.M;
-    const int nchunks = (M + KC - 1) / KC;
+    // one pass over the contraction dimension per operand pair; the accumulators carry over
+#pragma unroll
+    for (int pass = 0; pass < MatsT::NPASS; ++pass) {
+    const T* base[NP];
+    int64_t rs[NP], ks[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const Side<T>& sd = Shape::col_side(p) ? m.Q[pass] : m.R[pass];
+        base[p] = sd.p;
+        rs[p] = sd.rs;
+        ks[p] = sd.ks;
+    }
+    if (MatsT::NPASS > 1 && pass > 0) __syncthreads();      // every wavefront has left the previous pass's LDS
     if constexpr (FAST) {
         // Addresses for the assembly loop (layout and schedule: gen_asm_loops.py).  In LDS a chunk
         // buffer holds the used panels back to back, 64 rows of 128 bytes each, the 16-byte pieces of
@@ -373,13 +404,22 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
         constexpr int ES = (int)sizeof(T);
         typedef __attribute__((address_space(3))) unsigned char lds_byte;
         const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_byte*)lds;
+        // Column panels (the contraction index runs across memory rows; all operands of a launch are of
+        // one kind): a 16-byte piece then holds VEC consecutive panel rows at one k.  The 2 KB of a
+        // 16-row group hold its pieces in the order (k, group of VEC rows), so that a wavefront's operand
+        // read (16 rows x 4 k) covers 4 x 128 (64) contiguous bytes and a load instruction deposits, for 8
+        // (16) values of k, the 128 (64) contiguous bytes of 16 rows: no bank conflicts, no permutation.
+        const bool colp = ks[Shape::b_panel(0)] != 1;
+        constexpr int VEC = Cfg<T>::VEC;
         AsmLoopArgs g;
         {
             const uint32_t r16 = lane & 15, gq = lane >> 4, x = r16 & 7;
 #pragma unroll
             for (int j = 0; j < KS; ++j) {
                 uint32_t a;
-                if (ES == 8)       // element k = 4 ks + gq: piece (2 ks + gq/2) ^ x, half gq & 1
+                if (colp)          // element k = 4 j + gq of row r16: byte (k * 16 + r16) * ES of the group
+                    a = ((uint32_t)(4 * j + gq) * 16 + r16) * ES;
+                else if (ES == 8)  // element k = 4 ks + gq: piece (2 ks + gq/2) ^ x, half gq & 1
                     a = r16 * 128 + ((((gq >> 1) ^ (x & 1)) | (((uint32_t)j ^ (x >> 1)) << 1)) << 4) + (gq & 1) * 8;
                 else               // element k = 4 ks + gq: piece ks ^ x, word gq
                     a = r16 * 128 + (((uint32_t)j ^ x) << 4) + gq * 4;
@@ -388,25 +428,36 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
             }
         }
         g.nch = (uint32_t)(M / KC);                         // whole chunks; the rest follows below
-        g.step = (uint32_t)(KC * ES);
+        g.step = to_scalar((uint32_t)(KC * ES * ks[Shape::b_panel(0)]));   // (all operands of a launch advance alike)
         g.m0base = lds0 + (uint32_t)w * 1024;
         uint32_t go[10];
         int q = 0, np_used = 0;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             if (!((PANELS >> p) & 1u)) continue;
-            g.gP[np_used++] = base[p] + (int64_t)prow[p] * kTile * ld[p];
+            g.gP[np_used++] = to_scalar(base[p] + (int64_t)prow[p] * kTile * rs[p]);
+            const int rows_in = min(kTile, nrows[p] - prow[p] * kTile);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                // this lane's piece of the wavefront's 8 rows: row 8w + lane/8 of the half-panel,
-                // global piece (lane%8) ^ (lane/8) so that it lands at LDS position lane%8; the offset is
-                // relative to the panel's first row (64 rows of a matrix stay below 4 GiB: checked by
-                // the caller)
-                // (a panel that reaches beyond the matrix: its last row stands in for the missing ones;
-                // what is computed from them belongs to rows or columns of C that are never stored)
-                const int rows_in = min(kTile, nrows[p] - prow[p] * kTile);
-                const int64_t row = min(h * 32 + w * 8 + (lane >> 3), rows_in - 1);
-                go[q++] = (uint32_t)(row * ld[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
+                if (colp) {
+                    // LDS position (16-byte units) h * 256 + w * 64 + lane of the panel's chunk: 16-row
+                    // group 2 h + w / 2, piece (w % 2) * 64 + lane inside it = (k, group of VEC rows).
+                    // A panel that reaches beyond the matrix has a multiple of VEC rows inside (checked
+                    // by the caller); the last whole group of rows stands in for the missing ones.
+                    const int piece = (w & 1) * 64 + lane, per_k = 16 / VEC;
+                    const int k = piece / per_k;
+                    const int row = min((2 * h + (w >> 1)) * 16 + (piece % per_k) * VEC, rows_in - VEC);
+                    go[q++] = (uint32_t)(((int64_t)k * ks[p] + row) * ES);
+                } else {
+                    // this lane's piece of the wavefront's 8 rows: row 8w + lane/8 of the half-panel,
+                    // global piece (lane%8) ^ (lane/8) so that it lands at LDS position lane%8; the offset
+                    // is relative to the panel's first row (64 rows of a matrix stay below 4 GiB: checked
+                    // by the caller)
+                    // (a panel that reaches beyond the matrix: its last row stands in for the missing ones;
+                    // what is computed from them belongs to rows or columns of C that are never stored)
+                    const int64_t row = min(h * 32 + w * 8 + (lane >> 3), rows_in - 1);
+                    go[q++] = (uint32_t)(row * rs[p] * ES + (((lane & 7) ^ (lane >> 3)) << 4));
+                }
             }
         }
         AsmLoop<T, Shape, SLOTS>::run(acc, g, go);
@@ -417,8 +468,9 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
         const int nch = (M - k_begin + KC - 1) / KC;
         if (nch <= 0) return;
         Stager<T, NP, PANELS> st;
-        st.init(base, ld, nrows, prow, tid);
-        const bool aligned = vec_ok(m.R, m.ldr) && vec_ok(m.Q, m.ldq);
+        st.init(base, rs, ks, nrows, prow, tid);
+        const bool aligned = m.R[pass].ks == 1 && m.Q[pass].ks == 1 && vec_ok(m.R[pass].p, m.R[pass].rs) &&
+                             vec_ok(m.Q[pass].p, m.Q[pass].rs);
         st.load_checked(M, k_begin, aligned && k_begin + KC <= M, tid);
         st.store(lds, tid);
         __syncthreads();
@@ -455,6 +507,7 @@ __device__ __forceinline__ void block_body(const Mats<T>& m, const int (&prow)[S
     } else {
         checked_columns(0);
     }
+    }   // passes
 
     if (CAN_SLICE && sc.part != nullptr) {                  // uniform
         constexpr int NS = Shape::NSLOT;
@@ -569,8 +622,8 @@ template <> struct FastSets<RectShape> {
     }
 };
 
-template <typename T, class Shape, int IDX, bool CAN_SLICE>
-__device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Shape::NP], uint32_t pmask,
+template <typename T, class Shape, int IDX, bool CAN_SLICE, class MatsT>
+__device__ __forceinline__ bool try_fast(const MatsT& m, const int (&prow)[Shape::NP], uint32_t pmask,
                                          uint32_t dmask, T* lds, const SliceCtx<T>& sc)
 {
     if constexpr (IDX < FastSets<Shape>::N) {
@@ -596,8 +649,8 @@ __device__ __forceinline__ bool try_fast(const Mats<T>& m, const int (&prow)[Sha
 }
 
 // with_diag: tiles (r, r) belong to the block (their part on and below the diagonal)
-template <typename T, class Shape, bool CAN_SLICE = true>
-__device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* lds, const SliceCtx<T>& sc,
+template <typename T, class Shape, bool CAN_SLICE = true, class MatsT>
+__device__ __forceinline__ void run_block(const Item& it, const MatsT& m, T* lds, const SliceCtx<T>& sc,
                                           bool with_diag = false)
 {
     constexpr int NP = Shape::NP;
@@ -623,9 +676,17 @@ __device__ __forceinline__ void run_block(const Item& it, const Mats<T>& m, T* l
     const int64_t lim = (int64_t)1 << 32;
     // (rows need no alignment beyond that of an element: the loads into LDS take 16 bytes from any
     // element-aligned address, at full speed)
-    const bool fast_ok = m.M >= KC &&
-                         (int64_t)kTile * m.ldr * (int64_t)sizeof(T) < lim &&
-                         (int64_t)kTile * m.ldq * (int64_t)sizeof(T) < lim;
+    // (column panels: the KC memory rows of a chunk instead, and whole 16-byte pieces inside the matrix)
+    bool fast_ok = m.M >= KC;
+#pragma unroll
+    for (int pass = 0; pass < MatsT::NPASS; ++pass) {
+        const Side<T>&r = m.R[pass], &q = m.Q[pass];
+        const bool colp = r.ks != 1;
+        fast_ok = fast_ok && (q.ks != 1) == colp;
+        fast_ok = fast_ok && (colp ? KC * r.ks + kTile : kTile * r.rs) * (int64_t)sizeof(T) < lim &&
+                  (colp ? KC * q.ks + kTile : kTile * q.rs) * (int64_t)sizeof(T) < lim;
+        if (colp) fast_ok = fast_ok && r.rs == 1 && q.rs == 1 && m.nr % Cfg<T>::VEC == 0 && m.nq % Cfg<T>::VEC == 0;
+    }
     if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
     block_body<T, Shape, (1u << Shape::NSLOT) - 1, false, CAN_SLICE>(m, prow, pmask, dmask, lds, sc, true);
 }
@@ -639,13 +700,13 @@ struct SliceSpace {
     int* flag = nullptr;            // one int of LDS
 };
 
-template <typename T>
-__device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mats<T>& m0, T* lds,
+template <typename T, bool TRI = true, class MatsT>
+__device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const MatsT& m0, T* lds,
                                          const SliceSpace<T>& sp)
 {
     Item it;
     tbs_decode(plan, id, it);
-    Mats<T> m = m0;
+    MatsT m = m0;
     SliceCtx<T> sc;
     if (it.slices > 1 && it.kind != kEmpty) {
         // part `slice` of the columns of A, in whole chunks (the last part takes the ragged end)
@@ -653,8 +714,11 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
         const int64_t nch = (m0.M + KC - 1) / KC;
         const int64_t k0 = nch * it.slice / it.slices * KC;
         const int64_t k1 = (it.slice + 1 == it.slices) ? (int64_t)m0.M : nch * (it.slice + 1) / it.slices * KC;
-        m.R = m0.R + k0;
-        m.Q = m0.Q + k0;
+#pragma unroll
+        for (int pass = 0; pass < MatsT::NPASS; ++pass) {
+            m.R[pass].p = m0.R[pass].p + k0 * m0.R[pass].ks;
+            m.Q[pass].p = m0.Q[pass].p + k0 * m0.Q[pass].ks;
+        }
         m.M = (int)(k1 > k0 ? k1 - k0 : 0);
         sc.part = sp.ws + (size_t)it.ws_block * ((size_t)plan.ws_slices * 6 * 16 * kThreads);
         sc.ctr = sp.ctr + it.ws_block;
@@ -663,7 +727,7 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
         sc.slice = it.slice;
     }
     if (it.kind == kTri) {
-        run_block<T, TriShape>(it, m, lds, sc);
+        if constexpr (TRI) run_block<T, TriShape>(it, m, lds, sc);      // (plans of rectangles have none)
     } else if (it.kind == kRect) {
         run_block<T, RectShape>(it, m, lds, sc);
     } else if (it.kind == kRectDiag) {
@@ -678,17 +742,15 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
 
 // One workgroup per block of the plan (used when the plan has no more blocks than the launch may
 // have workgroups).
-template <typename T>
-__global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, int M, T alpha,
-                                                            const T* __restrict__ A, int64_t lda,
-                                                            T beta, T* __restrict__ C, int64_t ldc, T* ws,
+// NPASS, TRI: 1, true for SYRK and the Gram form; 2, false for SYR2K (rectangles only).
+template <typename T, int NPASS, bool TRI>
+__global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, NPASS> m, T* ws,
                                                             unsigned int* slice_ctr)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
     __shared__ int s_flag;
-    const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
     const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
-    run_item<T>(plan, (int32_t)blockIdx.x, m, reinterpret_cast<T*>(smem), sp);
+    run_item<T, TRI>(plan, (int32_t)blockIdx.x, m, reinterpret_cast<T*>(smem), sp);
 }
 
 // Persistent form: a fixed number of workgroups (at most one per compute unit; fewer when the caller
@@ -702,17 +764,14 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, int N, in
 // measured and dropped: the bytes fetched into the L2s did not change.  The workgroups of a die
 // drift apart by more chunks than its 4 MB L2 can hold for 28 blocks with six chunks in flight each.)
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, int N, int M, T alpha,
-                                                                       const T* __restrict__ A, int64_t lda,
-                                                                       T beta, T* __restrict__ C, int64_t ldc,
+template <typename T, int NPASS, bool TRI>
+__global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, Mats<T, NPASS> m,
                                                                        unsigned int* ctr, T* ws,
                                                                        unsigned int* slice_ctr)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
     __shared__ int32_t s_item;
     __shared__ int s_flag;
-    const Mats<T> m = {A, lda, N, A, lda, N, C, ldc, M, alpha, beta, true};
     const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
     for (;;) {
         __syncthreads();                        // the previous block's LDS reads and s_item are done with
@@ -720,7 +779,7 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
         __syncthreads();
         const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
         if (id >= plan.n_items) break;
-        run_item<T>(plan, id, m, reinterpret_cast<T*>(smem), sp);
+        run_item<T, TRI>(plan, id, m, reinterpret_cast<T*>(smem), sp);
     }
     if (threadIdx.x == 0) {
         __threadfence();
@@ -758,31 +817,48 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
         const int t = I * mr + r;
         it.rows[kRectCols + r] = (r < mr && t < Tm) ? t : -1;
     }
-    const Mats<T> m = {R, ldr, m_rows, Q, ldq, n_cols, C, ldc, K, alpha, beta, false};
+    const Mats<T> m = {{{R, ldr, 1}}, m_rows, {{Q, ldq, 1}}, n_cols, C, ldc, K, alpha, beta, false};
     run_block<T, RectShape, false>(it, m, lds, SliceCtx<T>{});
 }
 
 // `lease`: the counters of this launch (see acquire_counters); needed by the persistent form and by
 // plans with cut blocks.  Its event, if any, is attached to the kernel: it completes with the launch.
-template <typename T>
-hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                                int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* ws,
-                                const CounterLease& lease, hipStream_t stream)
+// NPASS = 1: C <- beta C + alpha A A^T (b unused); NPASS = 2: C <- beta C + alpha (A B^T + B A^T), plan
+// of rectangles only.
+template <typename T, int NPASS>
+hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
+                         const OperandDesc& b, double beta, void* C, int64_t ldc, int max_workgroups, void* ws,
+                         const CounterLease& lease, hipStream_t stream)
 {
     if (plan.n_items <= 0) return hipSuccess;
     if (plan.n_ws_blocks > kSliceCounters || (plan.n_ws_blocks > 0 && ws == nullptr)) return hipErrorInvalidValue;
     const bool persistent = max_workgroups > 0 && plan.n_items > max_workgroups;
     if ((persistent && lease.ctr == nullptr) || (plan.n_ws_blocks > 0 && lease.slice_ctr == nullptr))
         return hipErrorInvalidValue;
+    constexpr bool TRI = NPASS == 1;
+    Mats<T, NPASS> m;
+    const Side<T> sa = {(const T*)a.p, a.rs, a.ks}, sb = {(const T*)b.p, b.rs, b.ks};
+    m.R[0] = sa;
+    m.Q[0] = NPASS == 1 ? sa : sb;
+    if constexpr (NPASS == 2) {
+        m.R[1] = sb;
+        m.Q[1] = sa;
+    }
+    m.nr = m.nq = (int)N;
+    m.C = (T*)C;
+    m.ldc = ldc;
+    m.M = (int)M;
+    m.alpha = (T)alpha;
+    m.beta = (T)beta;
+    m.lower = true;
     if (!persistent) {
-        hipExtLaunchKernelGGL(tbs_syrk_kernel<T>, dim3((unsigned)plan.n_items), dim3(kThreads), 0, stream, nullptr,
-                              lease.done, 0, plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C, ldc,
-                              (T*)ws, lease.slice_ctr);
+        hipExtLaunchKernelGGL((tbs_syrk_kernel<T, NPASS, TRI>), dim3((unsigned)plan.n_items), dim3(kThreads), 0,
+                              stream, nullptr, lease.done, 0, plan, m, (T*)ws, lease.slice_ctr);
         return hipGetLastError();
     }
-    hipExtLaunchKernelGGL(tbs_syrk_persistent_kernel<T>, dim3((unsigned)max_workgroups), dim3(kThreads), 0, stream,
-                          nullptr, lease.done, 0, plan, (int)N, (int)M, (T)alpha, (const T*)A, lda, (T)beta, (T*)C,
-                          ldc, lease.ctr, (T*)ws, lease.slice_ctr);
+    hipExtLaunchKernelGGL((tbs_syrk_persistent_kernel<T, NPASS, TRI>), dim3((unsigned)max_workgroups),
+                          dim3(kThreads), 0, stream, nullptr, lease.done, 0, plan, m, lease.ctr, (T*)ws,
+                          lease.slice_ctr);
     return hipGetLastError();
 }
 
@@ -823,22 +899,26 @@ hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const vo
 // minutes): -DTBS_UNIT_SYRK or -DTBS_UNIT_GEMM with -DTBS_UNIT_TYPE=double|float instantiates one
 // launcher (and the kernels it launches), -DTBS_UNIT_DISPATCH defines the entry points that choose
 // between them; without any of these macros one translation unit holds everything.
+#define TBS_LAUNCH_SYRK_ARGS \
+    const Plan&, int64_t, int64_t, double, const OperandDesc&, const OperandDesc&, double, void*, int64_t, int, \
+        void*, const CounterLease&, hipStream_t
+#define TBS_LAUNCH_GEMM_ARGS \
+    int64_t, int64_t, int64_t, double, const void*, int64_t, const void*, int64_t, double, void*, int64_t, int, \
+        hipStream_t
 #if defined(TBS_UNIT_SYRK)
-template hipError_t launch_syrk_t<TBS_UNIT_TYPE>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
-                                                 void*, int64_t, int, void*, const CounterLease&, hipStream_t);
+template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 1>(TBS_LAUNCH_SYRK_ARGS);
+#elif defined(TBS_UNIT_SYR2K)
+template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 2>(TBS_LAUNCH_SYRK_ARGS);
 #elif defined(TBS_UNIT_GEMM)
-template hipError_t launch_gemm_t<TBS_UNIT_TYPE>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
-                                                 int64_t, double, void*, int64_t, int, hipStream_t);
+template hipError_t launch_gemm_t<TBS_UNIT_TYPE>(TBS_LAUNCH_GEMM_ARGS);
 #else
 #if defined(TBS_UNIT_DISPATCH)
-extern template hipError_t launch_syrk_t<double>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
-                                                 void*, int64_t, int, void*, const CounterLease&, hipStream_t);
-extern template hipError_t launch_syrk_t<float>(const Plan&, int64_t, int64_t, double, const void*, int64_t, double,
-                                                void*, int64_t, int, void*, const CounterLease&, hipStream_t);
-extern template hipError_t launch_gemm_t<double>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
-                                                 int64_t, double, void*, int64_t, int, hipStream_t);
-extern template hipError_t launch_gemm_t<float>(int64_t, int64_t, int64_t, double, const void*, int64_t, const void*,
-                                                int64_t, double, void*, int64_t, int, hipStream_t);
+extern template hipError_t launch_syrk_t<double, 1>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<float, 1>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<double, 2>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<float, 2>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_gemm_t<double>(TBS_LAUNCH_GEMM_ARGS);
+extern template hipError_t launch_gemm_t<float>(TBS_LAUNCH_GEMM_ARGS);
 #endif
 // ---- counters in device memory --------------------------------------------------------------------
 // One set per slot: ctr[2] of the persistent form (next block, workgroups done) and one counter per
@@ -927,14 +1007,27 @@ hipError_t static_scratch(unsigned char** out)
     return hipSuccess;
 }
 
-hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const void* A,
-                       int64_t lda, double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
+hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
+                       double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
                        const CounterLease& lease, hipStream_t stream)
 {
-    return f32 ? launch_syrk_t<float>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, lease,
-                                      stream)
-               : launch_syrk_t<double>(plan, N, M, alpha, A, lda, beta, C, ldc, max_workgroups, workspace, lease,
-                                       stream);
+    return f32 ? launch_syrk_t<float, 1>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups, workspace, lease,
+                                         stream)
+               : launch_syrk_t<double, 1>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups, workspace, lease,
+                                          stream);
+}
+
+hipError_t launch_syr2k(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
+                        const OperandDesc& b, double beta, void* C, int64_t ldc, int max_workgroups,
+                        const CounterLease& lease, hipStream_t stream)
+{
+    if (plan.n_ws_blocks > 0) return hipErrorInvalidValue;
+    for (int32_t sg = 0; sg < plan.nseg; ++sg)
+        if (plan.seg[sg].kind == kSegTri || plan.seg[sg].kind == kSegTriBase) return hipErrorInvalidValue;
+    return f32 ? launch_syrk_t<float, 2>(plan, N, M, alpha, a, b, beta, C, ldc, max_workgroups, nullptr, lease,
+                                         stream)
+               : launch_syrk_t<double, 2>(plan, N, M, alpha, a, b, beta, C, ldc, max_workgroups, nullptr, lease,
+                                          stream);
 }
 
 size_t syrk_workspace_bytes(bool f32, const Plan& plan)

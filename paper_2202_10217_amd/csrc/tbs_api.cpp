@@ -191,8 +191,8 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
             wgs = 0;
         }
     }
-    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc, wgs,
-                                          workspace, lease, stream);
+    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, tbs::OperandDesc{A, lda, 1}, beta, C,
+                                          ldc, wgs, workspace, lease, stream);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 
@@ -509,8 +509,77 @@ tbs_status tbs_syrk_lower_noalloc(tbs_dtype dtype, int64_t N, int64_t M, double 
     lease.slice_ctr = lease.ctr + 2;
     if (tbs::launch_fill_i32(reinterpret_cast<int32_t*>(base), 0, 2 + tbs::kSliceCounters, stream) != hipSuccess)
         return TBS_EHIP;
-    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, A, lda, beta, C, ldc,
-                                          persistent_workgroups(0), base + tbs::kStaticCounterBytes, lease, stream);
+    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, tbs::OperandDesc{A, lda, 1}, beta, C,
+                                          ldc, persistent_workgroups(0), base + tbs::kStaticCounterBytes, lease,
+                                          stream);
+    return e == hipSuccess ? TBS_OK : TBS_EHIP;
+}
+
+tbs_status tbs_syr2k_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A, int64_t lda,
+                           const void* B, int64_t ldb, double beta, void* C, int64_t ldc, void* hip_stream)
+{
+    const tbs_status st = check_syrk(dtype, N, M, A, lda, C, ldc);
+    if (st != TBS_OK) return st;
+    if (ldb < (M > 1 ? M : 1) || (N > 0 && M > 0 && B == nullptr)) return TBS_EINVAL;
+    if (N == 0) return TBS_OK;
+    const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const tbs::Plan* plan = cached_plan(T, true, dtype, M, false);      // rectangular blocks only
+    if (!plan) return TBS_EINVAL;
+    int wgs = persistent_workgroups(0);
+    tbs::CounterLease lease;
+    if (wgs > 0 && plan->n_items > wgs) {
+        if (tbs::acquire_counters(stream, &lease) != hipSuccess) return TBS_EHIP;
+        if (!lease.ctr) wgs = 0;                            // no counters free: one workgroup per block
+    }
+    const hipError_t e = tbs::launch_syr2k(dtype == TBS_F32, *plan, N, M, alpha, tbs::OperandDesc{A, lda, 1},
+                                           tbs::OperandDesc{B, ldb, 1}, beta, C, ldc, wgs, lease, stream);
+    return e == hipSuccess ? TBS_OK : TBS_EHIP;
+}
+
+// The Gram form: the order of C is the number of columns of A, the contraction runs down its rows.
+static tbs_status check_gram(tbs_dtype dtype, int64_t N, int64_t M, const void* A, int64_t lda, const void* C,
+                             int64_t ldc)
+{
+    if (!dtype_ok(dtype)) return TBS_EINVAL;
+    if (N < 0 || M < 0 || M > kMaxN || N > kMaxM) return TBS_EINVAL;
+    if (lda < (M > 1 ? M : 1) || ldc < (M > 1 ? M : 1)) return TBS_EINVAL;
+    if (N > 0 && M > 0 && A == nullptr) return TBS_EINVAL;
+    if (M > 0 && C == nullptr) return TBS_EINVAL;
+    return TBS_OK;
+}
+
+tbs_status tbs_gram_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_t* bytes)
+{
+    return tbs_syrk_lower_workspace(dtype, M, N, bytes);    // the plan of a SYRK of order M, contraction N
+}
+
+tbs_status tbs_gram_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha, const void* A, int64_t lda,
+                          double beta, void* C, int64_t ldc, void* workspace, size_t workspace_bytes,
+                          void* hip_stream)
+{
+    const tbs_status st = check_gram(dtype, N, M, A, lda, C, ldc);
+    if (st != TBS_OK) return st;
+    if (M == 0) return TBS_OK;
+    const int32_t T = (int32_t)((M + kTile - 1) / kTile);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const tbs::Plan* plan = nullptr;
+    const tbs_status ps = plan_for_call(T, false, dtype, N, workspace, workspace_bytes, &plan);
+    if (ps != TBS_OK) return ps;
+    int wgs = persistent_workgroups(0);
+    tbs::CounterLease lease;
+    if ((wgs > 0 && plan->n_items > wgs) || plan->n_ws_blocks > 0) {
+        if (tbs::acquire_counters(stream, &lease) != hipSuccess) return TBS_EHIP;
+        if (!lease.ctr) {
+            plan = cached_plan(T, false, dtype, N, false);
+            if (!plan) return TBS_EINVAL;
+            wgs = 0;
+        }
+    }
+    // panel row i of the operand is column i of A: rows one element apart, the contraction one
+    // leading dimension apart
+    const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, M, N, alpha, tbs::OperandDesc{A, 1, lda}, beta, C,
+                                          ldc, wgs, workspace, lease, stream);
     return e == hipSuccess ? TBS_OK : TBS_EHIP;
 }
 
