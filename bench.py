@@ -149,6 +149,10 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--only", action="store_true", help="skip the side workloads (profiling runs)")
     ap.add_argument("--preheat-ms", type=float, default=PREHEAT_MS)
+    ap.add_argument("--device-inputs", action="store_true",
+                    help="fill the matrices on the device with torch's generator instead of the seeded host "
+                         "generator (same shapes and distributions; for profiler runs, where only the access "
+                         "pattern matters and the host generator's time would be paid under the profiler)")
     ap.add_argument("--copy-bytes", type=int, default=0,
                     help="instead of the benchmark: run a plain device copy of this many bytes --steps "
                          "times (reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -178,6 +182,30 @@ def main():
         return 0
 
     def make(name, square=False):
+        if args.device_inputs:
+            op, N, M, dtype, alpha, beta, seed = inputs.CONFIGS[name]
+            tdt = torch.float64 if dtype == np.float64 else torch.float32
+            gen = torch.Generator(device="cuda").manual_seed(seed)
+            if op == "potrf":
+                w = Potrf.__new__(Potrf)
+                S = torch.rand((N, N), dtype=tdt, device="cuda", generator=gen) * 2 - 1
+                S = torch.tril(S, -1)
+                S = S + S.T
+                S.diagonal().fill_(float(N))
+                w.tb, w.torch, w.name, w.N, w.dname, w.dS = tb, torch, name, N, "f64", S
+                w.dW = torch.empty_like(S)
+                w.ws = torch.empty(tb.tbs_potrf_lower_workspace(tb.TBS_F64, N), dtype=torch.uint8, device="cuda")
+                w.flops = float(N) ** 3 / 3.0
+                return w
+            w = Syrk(tb, torch, name, np.zeros((1, 1), dtype=dtype), np.zeros((1, 1), dtype=dtype), alpha, beta, square)
+            w.N, w.M = N, M
+            w.dA = torch.randn((N, M), dtype=tdt, device="cuda", generator=gen) / (1.0 if N == M == 4096 else np.sqrt(M))
+            w.dC = torch.zeros((N, N), dtype=tdt, device="cuda") if beta == 0.0 else \
+                torch.rand((N, N), dtype=tdt, device="cuda", generator=gen) * 2 - 1
+            need = 0 if square else tb.tbs_syrk_lower_workspace(w.code, N, M)
+            w.ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need > 0 else False
+            w.flops = float(N) * float(N) * float(M)
+            return w
         op, A, C0, alpha, beta = inputs.make_config(name)
         return Potrf(tb, torch, name, C0) if op == "potrf" else Syrk(tb, torch, name, A, C0, alpha, beta, square)
 
@@ -210,7 +238,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": w.dname,
-        "data": "synthetic",
+        "data": "synthetic (device generator)" if args.device_inputs else "synthetic",
         "preheat_ms": round(heat, 1),
     }
     if is_potrf:

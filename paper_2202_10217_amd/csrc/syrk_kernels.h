@@ -8,9 +8,10 @@
 namespace tbs {
 
 constexpr int kSliceCounters = 512;      // cut blocks per plan (one device counter each)
+constexpr int kLaunchCounters = 16;      // of a persistent launch: next block, workgroups done, one per die
 
-// The device counters one launch may use: the pair of the persistent form, the counters of the cut
-// blocks, and the event that completes with the launch.  Empty (all null): none could be given.
+// The device counters one launch may use: the kLaunchCounters of the persistent form, the counters of
+// the cut blocks, and the event that completes with the launch.  Empty (all null): none could be given.
 struct CounterLease {
     unsigned int* ctr = nullptr;
     unsigned int* slice_ctr = nullptr;

@@ -757,12 +757,26 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, N
 // wants to keep units free for kernels of another stream) take blocks from the list in order through
 // a counter in device memory, which is what the hardware dispatcher does with one workgroup per
 // block, minus the cost of starting a workgroup for every block.  ctr[0] = next block, ctr[1] =
-// workgroups that have finished; the last one to finish sets both back to zero for the next launch
-// that uses the same pair.
+// workgroups that have finished; the last one to finish sets the counters back to zero for the next
+// launch that uses the same set.
 //
-// (A variant with one queue per accelerator die, each holding blocks that share panels of A, was
-// measured and dropped: the bytes fetched into the L2s did not change.  The workgroups of a die
-// drift apart by more chunks than its 4 MB L2 can hold for 28 blocks with six chunks in flight each.)
+// The Triangle Block Scheme one level up (Section 5.1 with the L2 of a die as fast memory): the first
+// plan.team_items items are groups of 32 triangle blocks on 28 tile rows (tbs_plan.h).  The workgroups
+// of a die (they share its L2) take the blocks of one group together: die d owns the groups d, d + 8,
+// ... and hands them out through its own counter ctr[2 + d]; a workgroup whose die has none left helps
+// the other dies in turn, so every block is taken exactly once whatever the placement of the
+// workgroups, and then all continue with the rest of the list through ctr[0].  Blocks of equal length
+// started together stay together, so a group's 28 panels are fetched into the L2 once for 32 blocks.
+constexpr int kTeams = 8;                  // accelerator dies, each with its own L2
+constexpr int kTeamCtr = 4;                // ctr[kTeamCtr + d]: blocks handed out of die d's groups
+static_assert(kTeamCtr + kTeams <= kLaunchCounters, "the counters of a launch fit their set");
+
+__device__ __forceinline__ int die_of_this_workgroup()
+{
+    uint32_t id;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(id));
+    return (int)(id % kTeams);
+}
 
 template <typename T, int NPASS, bool TRI>
 __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, Mats<T, NPASS> m,
@@ -773,19 +787,51 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan
     __shared__ int32_t s_item;
     __shared__ int s_flag;
     const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
+    if (plan.team_items > 0) {
+        const int32_t n_groups = plan.team_items / kGroupItems;
+        const int home = die_of_this_workgroup();
+        for (;;) {
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                // the home die's next block; when it has none left, the next block of the first die (in
+                // turn) whose counter, read first, says that it has (the atomic's result decides)
+                int32_t got = -1;
+                unsigned int seen[kTeams];
+#pragma unroll
+                for (int t = 0; t < kTeams; ++t) seen[t] = 0u;
+                for (int turn = 0; turn < kTeams && got < 0; ++turn) {
+                    const int t = (home + turn) % kTeams;
+                    const int32_t mine = ((n_groups - t + kTeams - 1) / kTeams) * kGroupItems;   // die t's blocks
+                    if (turn == 1) {
+#pragma unroll
+                        for (int u = 0; u < kTeams; ++u)
+                            seen[u] = __hip_atomic_load(&ctr[kTeamCtr + u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if (mine <= 0 || (int32_t)seen[t] >= mine) continue;
+                    const int32_t n = (int32_t)atomicAdd(&ctr[kTeamCtr + t], 1u);
+                    if (n < mine) got = ((n / kGroupItems) * kTeams + t) * kGroupItems + n % kGroupItems;
+                }
+                s_item = got;
+            }
+            __syncthreads();
+            const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
+            if (id < 0) break;
+            run_item<T, TRI>(plan, id, m, reinterpret_cast<T*>(smem), sp);
+        }
+    }
     for (;;) {
         __syncthreads();                        // the previous block's LDS reads and s_item are done with
         if (threadIdx.x == 0) s_item = (int32_t)atomicAdd(&ctr[0], 1u);
         __syncthreads();
-        const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
+        const int32_t id = plan.team_items + __builtin_amdgcn_readfirstlane(s_item);
         if (id >= plan.n_items) break;
         run_item<T, TRI>(plan, id, m, reinterpret_cast<T*>(smem), sp);
     }
     if (threadIdx.x == 0) {
         __threadfence();
-        if (atomicAdd(&ctr[1], 1u) == gridDim.x - 1) {  // every workgroup has left its loop
-            ctr[0] = 0u;
-            ctr[1] = 0u;
+        if (atomicAdd(&ctr[1], 1u) == gridDim.x - 1) {  // every workgroup has left its loops
+#pragma unroll
+            for (int c = 0; c < kLaunchCounters; ++c) ctr[c] = 0u;
             __threadfence();
         }
     }
@@ -921,12 +967,12 @@ extern template hipError_t launch_gemm_t<double>(TBS_LAUNCH_GEMM_ARGS);
 extern template hipError_t launch_gemm_t<float>(TBS_LAUNCH_GEMM_ARGS);
 #endif
 // ---- counters in device memory --------------------------------------------------------------------
-// One set per slot: ctr[2] of the persistent form (next block, workgroups done) and one counter per
-// cut block (parts finished).  All zero at load time; every launch leaves its set zero again (the last
+// One set per slot: ctr[kLaunchCounters] of the persistent form (next block, workgroups done, next
+// block of each die's groups) and one counter per cut block (parts finished).  All zero at load time; every launch leaves its set zero again (the last
 // workgroup of a persistent launch resets the pair, the workgroup that sums a block resets its
 // counter).  Which launch may use which slot is decided by SlotTable (counter_slots.h); the event of a
 // slot completes with the last launch that used it.
-static __device__ unsigned int g_syrk_counters[kCounterSlots][2];
+static __device__ unsigned int g_syrk_counters[kCounterSlots][kLaunchCounters];
 static __device__ unsigned int g_slice_counters[kCounterSlots][kSliceCounters];
 
 namespace {
@@ -974,7 +1020,7 @@ hipError_t acquire_counters(hipStream_t stream, CounterLease* out)
         e = hipEventCreateWithFlags(&dc.done[s], hipEventDisableTiming);
         if (e != hipSuccess) return e;
     }
-    out->ctr = dc.pairs + 2 * s;
+    out->ctr = dc.pairs + (size_t)kLaunchCounters * s;
     out->slice_ctr = dc.slices + (size_t)kSliceCounters * s;
     out->done = dc.done[s];
     return hipSuccess;
@@ -983,7 +1029,7 @@ hipError_t acquire_counters(hipStream_t stream, CounterLease* out)
 // ---- scratch memory of the entry point that allocates nothing ---------------------------------------
 // Held by every device the library runs on until the process ends.  In host code the name below is
 // only a handle for hipGetSymbolAddress; kernels receive the looked-up address as an argument.
-static_assert(kStaticCounterBytes >= (2 + kSliceCounters) * sizeof(unsigned int), "counters fit");
+static_assert(kStaticCounterBytes >= (kLaunchCounters + kSliceCounters) * sizeof(unsigned int), "counters fit");
 static __device__ __align__(256) unsigned char scratch[kStaticCounterBytes + kStaticWorkspaceBytes];
 
 hipError_t static_scratch(unsigned char** out)

@@ -45,14 +45,15 @@ int32_t compute_units()
 // They are read at every call and are part of the cache key, so a plan built under one setting is
 // never handed out under another.
 struct PlanEnv {
-    std::string costs, family, slices, tuning;
+    std::string costs, family, slices, tuning, groups;
     static PlanEnv read()
     {
         auto get = [](const char* name) {
             const char* v = std::getenv(name);
             return std::string(v ? v : "");
         };
-        return PlanEnv{get("TBS_PLAN_COSTS"), get("TBS_PLAN_FAMILY"), get("TBS_SYRK_SLICES"), get("TBS_PLAN_TUNING")};
+        return PlanEnv{get("TBS_PLAN_COSTS"), get("TBS_PLAN_FAMILY"), get("TBS_SYRK_SLICES"), get("TBS_PLAN_TUNING"),
+                       get("TBS_SYRK_DIE_GROUPS")};
     }
 };
 
@@ -63,7 +64,8 @@ struct PlanEnv {
 const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M, bool sliced)
 {
     static std::mutex mu;
-    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool, std::string, std::string, std::string, std::string>,
+    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool, std::string, std::string, std::string, std::string,
+                               std::string>,
                     tbs::Plan>
         cache;
     int32_t bucket = 0;
@@ -71,7 +73,7 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
     const PlanEnv env = PlanEnv::read();
     std::lock_guard<std::mutex> lock(mu);
     auto key = std::make_tuple(T, square, (int32_t)dtype, bucket, sliced, env.costs, env.family, env.slices,
-                               square ? std::string() : env.tuning);
+                               square ? std::string() : env.tuning, env.groups);
     auto it = cache.find(key);
     if (it == cache.end()) {
         const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
@@ -91,6 +93,15 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
         tbs::Plan p;
         // TBS_PLAN_FAMILY=cyclic: the paper's cyclic family only (no power-of-two moduli)
         const bool xor_family = !(!env.family.empty() && env.family[0] == 'c');
+        // Top-level triangle blocks in groups of 32 that one die takes together (they share 28 panels in
+        // its L2): less than half the bytes come in from the fabric, and the workgroups of a die run in
+        // step, epilogues included.  It pays when A is too large for the last-level cache, so that the
+        // fetches would go to HBM (N = 32768, M = 8192 fp32: 136 -> 62 GB fetched, 3 % faster); with a
+        // smaller A they are served by that cache anyway and the synchronised epilogues cost 1-2 %.
+        // TBS_SYRK_DIE_GROUPS=1 / 0 forces the groups on / off.
+        const double a_bytes = (double)T * kTile * (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 4.0 : 8.0);
+        bool die_groups = a_bytes > 192.0 * 1048576.0;
+        if (!env.groups.empty()) die_groups = env.groups[0] != '0';
         // blocks may be cut along the contraction dimension while a part keeps at least 8 chunks of
         // the smallest M of the bucket; TBS_SYRK_SLICES=0 turns that off, "levels,rows,...,tri,rect,
         // tail_blocks,tail" in TBS_PLAN_TUNING pins it
@@ -107,13 +118,14 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
             lv >= 0 && lv <= tbs::kMaxLevels && mr >= 1 && mr <= tbs::kRectRows && nc >= 1 && nc <= tbs::kRectCols) {
             tbs::PlanTuning tune{lv, mr, nc, base != 0, mrd, ncd};
             tune.xor_family = xor_family;
+            tune.die_groups = die_groups;
             if (!tbs::build_plan(T, tune, &p)) return nullptr;
             if (max_slices > 1 && (st > 1 || sr > 1 || (tb > 0 && ts > 1))) {
                 tbs::Plan q;
                 if (tbs::apply_slicing(p, tbs::Slicing{st, sr, tb, ts}, &q)) p = q;
             }
         } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family, max_slices,
-                                     slice_us / tile_us, per_part_us / tile_us)) {
+                                     slice_us / tile_us, per_part_us / tile_us, die_groups)) {
             return nullptr;
         }
         it = cache.emplace(key, p).first;
@@ -506,8 +518,9 @@ tbs_status tbs_syrk_lower_noalloc(tbs_dtype dtype, int64_t N, int64_t M, double 
     // cleared by a kernel on the caller's stream (no memset node: the call may be recorded into a graph)
     tbs::CounterLease lease;
     lease.ctr = reinterpret_cast<unsigned int*>(base);
-    lease.slice_ctr = lease.ctr + 2;
-    if (tbs::launch_fill_i32(reinterpret_cast<int32_t*>(base), 0, 2 + tbs::kSliceCounters, stream) != hipSuccess)
+    lease.slice_ctr = lease.ctr + tbs::kLaunchCounters;
+    if (tbs::launch_fill_i32(reinterpret_cast<int32_t*>(base), 0, tbs::kLaunchCounters + tbs::kSliceCounters, stream) !=
+        hipSuccess)
         return TBS_EHIP;
     const hipError_t e = tbs::launch_syrk(dtype == TBS_F32, *plan, N, M, alpha, tbs::OperandDesc{A, lda, 1}, beta, C,
                                           ldc, persistent_workgroups(0), base + tbs::kStaticCounterBytes, lease,

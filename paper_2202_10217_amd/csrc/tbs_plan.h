@@ -37,6 +37,7 @@ constexpr int kMaxSegs = 28;
 constexpr int kRectRows = 2;     // rectangular block: at most 2 x 3 tiles
 constexpr int kRectCols = 3;
 constexpr int kMaxPanels = 5;    // panels of A a block can stage (k, or kRectRows + kRectCols)
+constexpr int kGroupItems = 32;  // blocks of a group that the workgroups of one die take together
 
 // kRect: tiles (r, q) of the block's rows x columns with q < r.  kRectDiag: q <= r, where of a tile
 // (r, r) only the part on and below the diagonal belongs to the block.
@@ -65,6 +66,12 @@ struct Seg {
     // of the enumeration described above (a list of blocks may be cut into two segments that are
     // sliced differently).  `ws0`: number of this segment's first block among all sliced blocks.
     int32_t slices, t0, ws0;
+    // kSegTri, level 0, XOR family with c >= 8: the c^2 blocks are enumerated in groups of 32,
+    // (i / 8, j / 4) outermost and (i % 8, j % 4) inside a group.  The blocks of a group lie on 28 tile
+    // rows instead of 128 (j: 4 values; i, i XOR j and i XOR x j: 8 values each, because the low three
+    // bits form a subspace that contains {0, 1, x, x + 1} and x times it): a group is a triangle block
+    // one level up in the sense of Section 5.1, for a fast memory shared by 32 compute units.
+    int32_t group;
 };
 
 struct Plan {
@@ -74,6 +81,8 @@ struct Plan {
     int32_t n_items;
     int32_t c[kMaxLevels];      // modulus of each level that has triangle blocks
     int32_t fam[kMaxLevels];    // 0: cyclic family; m > 0: the XOR family with c = 2^m
+    int32_t team_items;         // the first team_items items (a multiple of 32, whole groups of segment 0)
+                                // are handed out group by group to the workgroups of one die (0: none)
     int32_t n_ws_blocks;        // sliced blocks (each owns a stretch of the workspace)
     int32_t ws_slices;          // largest `slices` of any segment (the workspace stride per block)
     Seg seg[kMaxSegs];
@@ -125,7 +134,13 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
         const int32_t c = p.c[sg.level];
         const int32_t z = t / (c * c);
         const int32_t ij = t - z * c * c;
-        const int32_t i = ij / c, j = ij - i * c;
+        int32_t i = ij / c, j = ij - i * c;
+        if (sg.group) {                             // groups of 32 blocks that share tile rows
+            const int32_t g = ij >> 5, q = ij & 31, per_row = c >> 2;
+            const int32_t gi = g / per_row, gj = g - gi * per_row;
+            i = gi * 8 + (q >> 2);
+            j = gj * 4 + (q & 3);
+        }
         const int32_t base = zone_base(p, sg.level, z);
         it.kind = kTri;
         it.nrow = kK;

@@ -94,6 +94,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
             s.kind = kSegTri;
             s.level = level;
             s.count = (int32_t)(nz * c * c);
+            s.group = (tune.die_groups && level == 0 && fam >= 3) ? 1 : 0;
             tri.push_back(s);
             const int32_t done = k * c, l = Tl - done;
             if (l > 0) {                                    // the last l tile rows
@@ -139,8 +140,18 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
     p.n_items = first;
     p.n_ws_blocks = 0;
     p.ws_slices = 1;
+    set_team_items(&p);
     *out = p;
     return true;
+}
+
+void set_team_items(Plan* plan)
+{
+    plan->team_items = 0;
+    if (plan->nseg < 1) return;
+    const Seg& s = plan->seg[0];
+    if (s.kind == kSegTri && s.group && s.level == 0 && s.first == 0 && s.t0 == 0 && s.slices <= 1)
+        plan->team_items = s.count / kGroupItems * kGroupItems;
 }
 
 bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
@@ -190,6 +201,7 @@ bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
     p.n_items = first;
     p.n_ws_blocks = ws;
     p.ws_slices = smax;
+    set_team_items(&p);
     *out = p;
     return true;
 }
@@ -231,7 +243,7 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, doub
 }
 
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family,
-                 int32_t max_slices, double slice_overhead_tiles, double slice_per_part_tiles)
+                 int32_t max_slices, double slice_overhead_tiles, double slice_per_part_tiles, bool die_groups)
 {
     if (square) {
         // rectangles only; for small matrices the block shape with the shortest simulated makespan
@@ -253,6 +265,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
     }
     PlanTuning coarse{kMaxLevels, kRectRows, kRectCols, true};
     coarse.xor_family = xor_family;
+    coarse.die_groups = die_groups;
     if (!build_plan(T, coarse, out)) return false;
     // with many blocks per compute unit the granularity of the tail does not matter
     const double per_unit = 0.5 * (double)T * (double)T / (double)std::max(ncu, 1);
@@ -301,6 +314,7 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
                 for (int32_t nct = kRectCols; nct >= 1; --nct) {
                     PlanTuning tune{levels, sh[0], sh[1], false, mrt, nct};
                     tune.xor_family = xor_family;
+                    tune.die_groups = die_groups;
                     Plan cand;
                     if (!build_plan(T, tune, &cand)) continue;
                     const double span = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);

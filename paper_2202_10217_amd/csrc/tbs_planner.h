@@ -18,6 +18,7 @@ struct PlanTuning {
     int32_t mr_deep = 0, nc_deep = 0;   // shape of the rectangles of triangular regions (0: as mr, nc);
                                         // one tile row high whenever they carry the diagonal tiles
     bool xor_family = true;  // levels may use c = 2^m with the XOR family where that covers more rows
+    bool die_groups = true;  // top-level blocks of the XOR family in groups of 32 that share tile rows
 };
 
 // How the blocks of a plan are cut along the contraction dimension (1 = not at all): all triangle
@@ -28,6 +29,9 @@ struct Slicing {
 };
 constexpr int32_t kMaxSliceBlocks = 512;   // sliced blocks per plan (each has a counter and workspace)
 constexpr int32_t kMaxSlices = 32;
+
+// Sets plan->team_items: the leading whole groups of segment 0 if that segment is grouped and not cut.
+void set_team_items(Plan* plan);
 
 // Rewrites the segments of an unsliced plan for the given slicing; false if it does not fit the
 // descriptor (too many segments or sliced blocks).
@@ -47,7 +51,8 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
 // a part of a block cut into S parts costs `slice_overhead_tiles + S * slice_per_part_tiles` on top
 // (storing the part; the last part to finish sums all of them).
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family = true,
-                 int32_t max_slices = 1, double slice_overhead_tiles = 0.03, double slice_per_part_tiles = 0.0);
+                 int32_t max_slices = 1, double slice_overhead_tiles = 0.03, double slice_per_part_tiles = 0.0,
+                 bool die_groups = true);
 
 // Makespan, in tile units, of dispatching the plan's blocks in order onto ncu units.
 double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles = 0.03,

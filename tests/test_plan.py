@@ -106,6 +106,40 @@ def test_every_pinned_tuning_covers_the_triangle_exactly_once(idx, monkeypatch):
         assert tb.tbs_syrk_lower_query(tb.TBS_F32, N, 777)["n_diag_tiles"] == T
 
 
+@pytest.mark.parametrize("N,M", [(4096, 4096), (16384, 512), (32768, 8192), (8192, 64)])
+def test_groups_of_32_top_level_blocks_share_their_tile_rows(N, M, monkeypatch):
+    # the top-level blocks of the XOR family are listed in groups of 32 that lie on 28 tile rows (a
+    # triangle block one level up, Section 5.1 with the L2 of a die as fast memory: 28 panels for 32
+    # blocks instead of 128); TBS_SYRK_DIE_GROUPS=0 lists them in plain (i, j) order, where 32
+    # consecutive blocks need many more; both orders hold the same blocks.  (By default the library groups
+    # them when A is larger than the last-level cache can serve.)
+    dt = tb.TBS_F32 if N == 32768 else tb.TBS_F64
+    monkeypatch.setenv("TBS_SYRK_DIE_GROUPS", "1")
+    items = tb.tbs_syrk_lower_enumerate(dt, N, M, 2)
+    info = tb.tbs_syrk_lower_query(dt, N, M, 2)
+    c = info["c"]
+    assert info["family"] >= 3 and c >= 8
+    top = items[:c * c]
+    assert (top[:, 0] == KIND_TRI).all() and (top[:, 1] == K).all()
+    rows_needed = []
+    for g in range(c * c // 32):
+        grp = top[32 * g:32 * g + 32, 3:3 + K]
+        assert len({tuple(r) for r in grp.tolist()}) == 32
+        rows_needed.append(len(np.unique(grp)))
+        assert [len(np.unique(grp[:, u])) for u in range(K)] == [4, 8, 8, 8]
+    assert max(rows_needed) == 28
+    monkeypatch.setenv("TBS_SYRK_DIE_GROUPS", "0")
+    plain = tb.tbs_syrk_lower_enumerate(dt, N, M, 2)
+    assert len(plain) == len(items)
+    assert {tuple(r) for r in plain[:c * c, 3:3 + K].tolist()} == {tuple(r) for r in top[:, 3:3 + K].tolist()}
+    assert np.array_equal(plain[c * c:], items[c * c:])
+    spread = [len(np.unique(plain[32 * g:32 * g + 32, 3:3 + K])) for g in range(c * c // 32)]
+    assert min(spread) >= 50
+    monkeypatch.delenv("TBS_SYRK_DIE_GROUPS")
+    default = tb.tbs_syrk_lower_enumerate(dt, N, M, 2)
+    assert np.array_equal(default, items if N * M * (4 if dt == tb.TBS_F32 else 8) > 192 << 20 else plain)
+
+
 def test_empty_matrix():
     assert len(tb.tbs_syrk_lower_enumerate(tb.TBS_F64, 0, 5)) == 0
 
