@@ -209,6 +209,11 @@ tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32
  *   device on first use (default priority) and keeps; their work is ordered before and after the
  *   caller's stream by events, so the caller sees an ordinary stream-ordered call.  Calls from
  *   several host threads on one device are enqueued one after the other.
+ *   Inside a panel the block columns are processed right-looking (Algorithm 5 again, with a smaller
+ *   block); the environment variable TBS_POTRF_PANEL=left, read at every call, selects the
+ *   left-looking order (a block column first receives all updates of the panel's earlier block
+ *   columns, then is factored and solved: every entry of the panel is written once, as Section 5.2.2
+ *   accounts the panel steps).  Same results up to the order of the floating-point sums.
  * ---------------------------------------------------------------------------------------------- */
 tbs_status tbs_potrf_lower_workspace(tbs_dtype dtype, int64_t N, size_t* bytes);
 

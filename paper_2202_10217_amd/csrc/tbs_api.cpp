@@ -258,6 +258,12 @@ struct Lbc {
     // better use of the few compute units the panel stream has next to a long trailing update.
     int64_t fused_trsm_rows = 6144;
     int64_t wide_rows = 8192;   // trailing matrices at least this tall get double-width panels
+    // Inside a panel: right-looking (a block column is factored and solved, then the rest of the panel is
+    // updated with it: Algorithm 5 again) or left-looking (a block column first receives the updates of
+    // all earlier block columns of the panel in one product, then is factored and solved: every entry of
+    // the panel is written once, the rule by which Section 5.2.2 accounts the panel steps).  Same
+    // operations on the same values either way; TBS_POTRF_PANEL=left selects the second.
+    bool left_panel = false;
     bool piecewise_solve = true;   // solve of the rows below block by block on a third stream
     int64_t piecewise_width = 1024; // ... for panels up to this width (at most kSolvePieces diagonal blocks)
     hipError_t err = hipSuccess;
@@ -309,13 +315,27 @@ struct Lbc {
         const int64_t B = block_for(n);
         for (int64_t p0 = 0; p0 < n; p0 += B) {
             const int64_t nb = (B < n - p0) ? B : n - p0;
-            potrf(off + p0, nb, st);                                    // A[I0,I0] <- CHOL
             const int64_t rest = n - p0 - nb, row0 = off + p0 + nb;
+            if (left_panel && p0 > 0) update_block_column(off, p0, nb, rest, st);
+            potrf(off + p0, nb, st);                                    // A[I0,I0] <- CHOL
             if (rest <= 0) continue;
             trsm(row0, rest, off + p0, nb, st);                         // A[I1,I0] <- TRSM
-            note(syrk_impl(false, dtype, rest, nb, -1.0, at(row0, off + p0), lda, 1.0, at(row0, row0), lda,
-                           st));                                        // A[I1,I1] <- TBS
+            if (!left_panel)
+                note(syrk_impl(false, dtype, rest, nb, -1.0, at(row0, off + p0), lda, 1.0, at(row0, row0), lda,
+                               st));                                    // A[I1,I1] <- TBS
         }
+    }
+
+    // Left-looking step inside the panel that starts at `off`: block column [p0, p0 + nb) of the panel
+    // (its diagonal block and the `rest` panel rows below it) minus the products with the p0 columns
+    // left of it.
+    void update_block_column(int64_t off, int64_t p0, int64_t nb, int64_t rest, hipStream_t st)
+    {
+        note(syrk_impl(false, dtype, nb, p0, -1.0, at(off + p0, off), lda, 1.0, at(off + p0, off + p0), lda, st));
+        if (rest > 0)
+            note(tbs::launch_gemm_nt(dtype == TBS_F32, rest, nb, p0, -1.0, at(off + p0 + nb, off), lda,
+                                     at(off + p0, off), lda, 1.0, at(off + p0 + nb, off + p0), lda, compute_units(),
+                                     st));
     }
 
     // The panel A[off : off+n, off : off+n] factored on the panel stream as in potrf(), and, one
@@ -337,6 +357,7 @@ struct Lbc {
             // the last block column of the solve stays on the panel stream (it is what the next step
             // waits for, and a hand-over between streams costs about 12 us)
             hipStream_t st = solve;
+            if (left_panel && p0 > 0) update_block_column(off, p0, nb, n - p0 - nb, la->panel);
             if (!last) {
                 if (nb <= 2 * kTile) {                                  // the kernel's completion is the event
                     note(tbs::launch_potrf_block(f32, (int)nb, at(off + p0, off + p0), lda, info,
@@ -359,7 +380,8 @@ struct Lbc {
             const int64_t rest = n - p0 - nb, r1 = off + p0 + nb;
             if (rest <= 0) continue;
             trsm(r1, rest, off + p0, nb, la->panel);
-            note(syrk_impl(false, dtype, rest, nb, -1.0, at(r1, off + p0), lda, 1.0, at(r1, r1), lda, la->panel));
+            if (!left_panel)
+                note(syrk_impl(false, dtype, rest, nb, -1.0, at(r1, off + p0), lda, 1.0, at(r1, r1), lda, la->panel));
         }
     }
 
@@ -707,6 +729,7 @@ tbs_status tbs_potrf_lower(tbs_dtype dtype, int64_t N, void* A, int64_t lda, voi
         const long v = std::atol(e);
         if (v >= 64) ctx.piecewise_width = v;
     }
+    if (const char* e = std::getenv("TBS_POTRF_PANEL")) ctx.left_panel = e[0] == 'l';
     if (const char* e = std::getenv("TBS_POTRF_FUSED_ROWS")) {
         const long v = std::atol(e);
         if (v >= 0) ctx.fused_trsm_rows = v;

@@ -193,6 +193,44 @@ def test_double_width_panels_recover_an_integer_factor_exactly(tb, N, wide_rows,
     assert np.array_equal(out[np.triu_indices(N, 1)], S[np.triu_indices(N, 1)])
 
 
+# The left-looking panel (TBS_POTRF_PANEL=left, read at every call): every block column of a panel first
+# receives the updates of the earlier block columns of that panel, then is factored and solved.
+@pytest.mark.parametrize("N", [130, 700, 1536, 2500, 4133])
+def test_left_looking_panel_against_the_oracle(tb, N, monkeypatch):
+    monkeypatch.setenv("TBS_POTRF_PANEL", "left")
+    S0 = inputs.spd_diag_dominant(N, seed=N)
+    S = S0.copy()
+    S[np.triu_indices(N, 1)] = np.nan
+    info, out = _factor(tb, S)
+    assert info == 0
+    iu, il = np.triu_indices(N, 1), np.tril_indices(N)
+    assert np.isnan(out[iu]).all(), "upper triangle was modified"
+    Lo = S0.copy()
+    assert oracle.potrf_lower(Lo) == 0
+    L = np.tril(out)
+    assert oracle.llt_residual(L, S0) <= 1e-13
+    assert np.abs(L[il] - Lo[il]).max() <= 1e-12 * np.abs(Lo[il]).max()
+
+
+@pytest.mark.parametrize("N,wide_rows", [(1100, 8192), (3700, 512), (6600, 8192)])
+def test_left_looking_panel_recovers_an_integer_factor_exactly(tb, N, wide_rows, monkeypatch):
+    monkeypatch.setenv("TBS_POTRF_PANEL", "left")
+    monkeypatch.setenv("TBS_POTRF_WIDE_ROWS", str(wide_rows))
+    rng = np.random.default_rng(N)
+    G = np.tril(rng.integers(-1, 2, size=(N, N))).astype(np.float64)
+    np.fill_diagonal(G, rng.integers(1, 3, size=N))
+    S = G @ G.T
+    info, out = _factor(tb, S)
+    assert info == 0
+    assert np.array_equal(np.tril(out), G)
+    S[700, 700] -= 1.0 if N > 700 else 0.0                  # a failed pivot is still reported at its index
+    if N > 700:
+        G2 = np.tril(np.ones((N, N)))
+        S2 = G2 @ G2.T
+        S2[700, 700] -= 1.0
+        assert _factor(tb, S2)[0] == 701
+
+
 def test_calls_on_two_streams_without_waiting_in_between(tb):
     # two factorisations enqueued back to back on different streams of the caller (no synchronisation
     # between the calls, info not requested): the library's own streams and events are shared by all calls
