@@ -132,9 +132,12 @@ def side_entry(w, wall_ms, ev_ms, steps, warmup, with_copy=False):
     # events around the factorisation alone
     ms = ev_ms if with_copy else wall_ms
     tf = w.flops / (ms * 1e-3) / 1e12
-    return {"tflops": round(tf, 3), "ms_per_step": round(ms, 4), "kernel_ms": round(ev_ms, 4), "steps": steps,
-            "warmup": warmup, "dtype": w.dname, "peak": PEAK_TFLOPS[w.dname],
-            "frac": round(w.flops / (ev_ms * 1e-3) / 1e12 / PEAK_TFLOPS[w.dname], 4)}
+    out = {"tflops": round(tf, 3), "ms_per_step": round(ms, 4), "kernel_ms": round(ev_ms, 4), "steps": steps,
+           "warmup": warmup, "dtype": w.dname, "peak": PEAK_TFLOPS[w.dname],
+           "frac": round(w.flops / (ev_ms * 1e-3) / 1e12 / PEAK_TFLOPS[w.dname], 4)}
+    if isinstance(w, Syrk):                                 # HBM bytes per launch, where a summary is committed
+        out["traffic"], out["traffic_source"] = profile_traffic(w.name, w.square)
+    return out
 
 
 def main():
