@@ -41,7 +41,7 @@ def profile_traffic(workload, square):
     shape = re.search(r"n\d+_m\d+", workload)
     if not shape:
         return None, None
-    name = f"tbs_syrk_persistent_kernel_{dt}_{shape.group(0)}.md"
+    name = f"tbs_syrk_kernel_{dt}_{shape.group(0)}.md"
     path = os.path.join(ROOT, "profiles", name)
     key = "traffic_bytes_per_launch_square" if square else "traffic_bytes_per_launch"
     try:
@@ -261,7 +261,7 @@ def main():
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "peak_source": "published",
                            "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                            "traffic": traffic, "traffic_source": source,
-                           "kernel": "tbs_syrk_persistent_kernel", "kernel_ms": round(kern_ms, 4),
+                           "kernel": "tbs_syrk_kernel (persistent form)", "kernel_ms": round(kern_ms, 4),
                            "flops_per_launch": w.flops}
         out["io_model"] = {"S_C_elems": info["S_C_elems"], "S_res_elems": info["S_res_elems"],
                            "A_bytes_plan": info["A_elems"] * es, "C_bytes_read": info["C_elems"] * es * (w.beta != 0),

@@ -383,14 +383,18 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
         for (int rb = 0; rb < 4; ++rb) acc[s][rb] = acc_t{0, 0, 0, 0};
 
     const int M = m.M;
-    // one pass over the contraction dimension per operand pair; the accumulators carry over
+    // one pass over the contraction dimension per operand pair; the accumulators carry over (the
+    // operands of a pass are chosen by
+    // comparison, not by indexing, so that the kernel's arguments stay in registers)
 #pragma unroll
     for (int pass = 0; pass < MatsT::NPASS; ++pass) {
+    const Side<T> side_r = (MatsT::NPASS > 1 && pass > 0) ? m.R[MatsT::NPASS - 1] : m.R[0];
+    const Side<T> side_q = (MatsT::NPASS > 1 && pass > 0) ? m.Q[MatsT::NPASS - 1] : m.Q[0];
     const T* base[NP];
     int64_t rs[NP], ks[NP];
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-        const Side<T>& sd = Shape::col_side(p) ? m.Q[pass] : m.R[pass];
+        const Side<T>& sd = Shape::col_side(p) ? side_q : side_r;
         base[p] = sd.p;
         rs[p] = sd.rs;
         ks[p] = sd.ks;
@@ -469,8 +473,8 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
         if (nch <= 0) return;
         Stager<T, NP, PANELS> st;
         st.init(base, rs, ks, nrows, prow, tid);
-        const bool aligned = m.R[pass].ks == 1 && m.Q[pass].ks == 1 && vec_ok(m.R[pass].p, m.R[pass].rs) &&
-                             vec_ok(m.Q[pass].p, m.Q[pass].rs);
+        const bool aligned = side_r.ks == 1 && side_q.ks == 1 && vec_ok(side_r.p, side_r.rs) &&
+                             vec_ok(side_q.p, side_q.rs);
         st.load_checked(M, k_begin, aligned && k_begin + KC <= M, tid);
         st.store(lds, tid);
         __syncthreads();
@@ -740,33 +744,28 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
     }
 }
 
-// One workgroup per block of the plan (used when the plan has no more blocks than the launch may
-// have workgroups).
-// NPASS, TRI: 1, true for SYRK and the Gram form; 2, false for SYR2K (rectangles only).
-template <typename T, int NPASS, bool TRI>
-__global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, NPASS> m, T* ws,
-                                                            unsigned int* slice_ctr)
-{
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
-    __shared__ int s_flag;
-    const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
-    run_item<T, TRI>(plan, (int32_t)blockIdx.x, m, reinterpret_cast<T*>(smem), sp);
-}
-
-// Persistent form: a fixed number of workgroups (at most one per compute unit; fewer when the caller
-// wants to keep units free for kernels of another stream) take blocks from the list in order through
-// a counter in device memory, which is what the hardware dispatcher does with one workgroup per
-// block, minus the cost of starting a workgroup for every block.  ctr[0] = next block, ctr[1] =
-// workgroups that have finished; the last one to finish sets the counters back to zero for the next
-// launch that uses the same set.
+// The SYRK kernel.  NPASS, TRI: 1, true for SYRK and the Gram form; 2, false for SYR2K (rectangles only).
+//
+// ctr == nullptr: one workgroup per block of the plan (used when the plan has no more blocks than the
+// launch may have workgroups): workgroup b runs item b.
+//
+// Persistent form (ctr != nullptr): a fixed number of workgroups (at most one per compute unit; fewer
+// when the caller wants to keep units free for kernels of another stream) take blocks from the list in
+// order through a counter in device memory, which is what the hardware dispatcher does with one
+// workgroup per block, minus the cost of starting a workgroup for every block.  ctr[0] = next block,
+// ctr[1] = workgroups that have finished; the last one to finish sets the counters back to zero for the
+// next launch that uses the same set.
 //
 // The Triangle Block Scheme one level up (Section 5.1 with the L2 of a die as fast memory): the first
 // plan.team_items items are groups of 32 triangle blocks on 28 tile rows (tbs_plan.h).  The workgroups
 // of a die (they share its L2) take the blocks of one group together: die d owns the groups d, d + 8,
-// ... and hands them out through its own counter ctr[2 + d]; a workgroup whose die has none left helps
-// the other dies in turn, so every block is taken exactly once whatever the placement of the
+// ... and hands them out through its own counter ctr[kTeamCtr + d]; a workgroup whose die has none left
+// helps the other dies in turn, so every block is taken exactly once whatever the placement of the
 // workgroups, and then all continue with the rest of the list through ctr[0].  Blocks of equal length
 // started together stay together, so a group's 28 panels are fetched into the L2 once for 32 blocks.
+//
+// (All three ways of choosing the next block feed one loop with one call of run_item: the block code is
+// large, and every further call site would be another copy of it to compile.)
 constexpr int kTeams = 8;                  // accelerator dies, each with its own L2
 constexpr int kTeamCtr = 4;                // ctr[kTeamCtr + d]: blocks handed out of die d's groups
 static_assert(kTeamCtr + kTeams <= kLaunchCounters, "the counters of a launch fit their set");
@@ -779,57 +778,68 @@ __device__ __forceinline__ int die_of_this_workgroup()
 }
 
 template <typename T, int NPASS, bool TRI>
-__global__ __launch_bounds__(kThreads) void tbs_syrk_persistent_kernel(Plan plan, Mats<T, NPASS> m,
-                                                                       unsigned int* ctr, T* ws,
-                                                                       unsigned int* slice_ctr)
+__global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, NPASS> m, unsigned int* ctr, T* ws,
+                                                            unsigned int* slice_ctr)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kLdsBytes];
     __shared__ int32_t s_item;
     __shared__ int s_flag;
     const SliceSpace<T> sp = {ws, slice_ctr, &s_flag};
-    if (plan.team_items > 0) {
-        const int32_t n_groups = plan.team_items / kGroupItems;
-        const int home = die_of_this_workgroup();
-        for (;;) {
-            __syncthreads();
+    const bool persistent = ctr != nullptr;
+    const int32_t n_groups = persistent ? plan.team_items / kGroupItems : 0;
+    const int home = die_of_this_workgroup();
+    bool groups_left = n_groups > 0, first = true;
+    for (;;) {
+        int32_t id = -1;
+        if (!persistent) {
+            if (first) id = (int32_t)blockIdx.x;
+            first = false;
+        } else {
+            __syncthreads();                    // the previous block's LDS reads and s_item are done with
             if (threadIdx.x == 0) {
-                // the home die's next block; when it has none left, the next block of the first die (in
-                // turn) whose counter, read first, says that it has (the atomic's result decides)
                 int32_t got = -1;
-                unsigned int seen[kTeams];
+                if (groups_left) {
+                    // the home die's next block; when it has none left, the next block of the first die
+                    // (in turn) whose counter, read first, says that it has (the atomic's result decides)
+                    unsigned int seen[kTeams];
 #pragma unroll
-                for (int t = 0; t < kTeams; ++t) seen[t] = 0u;
-                for (int turn = 0; turn < kTeams && got < 0; ++turn) {
-                    const int t = (home + turn) % kTeams;
-                    const int32_t mine = ((n_groups - t + kTeams - 1) / kTeams) * kGroupItems;   // die t's blocks
-                    if (turn == 1) {
+                    for (int t = 0; t < kTeams; ++t) seen[t] = 0u;
+                    for (int turn = 0; turn < kTeams && got < 0; ++turn) {
+                        const int t = (home + turn) % kTeams;
+                        const int32_t mine = ((n_groups - t + kTeams - 1) / kTeams) * kGroupItems;   // die t's blocks
+                        if (turn == 1) {
 #pragma unroll
-                        for (int u = 0; u < kTeams; ++u)
-                            seen[u] = __hip_atomic_load(&ctr[kTeamCtr + u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            for (int u = 0; u < kTeams; ++u)
+                                seen[u] = __hip_atomic_load(&ctr[kTeamCtr + u], __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                        if (mine <= 0 || (int32_t)seen[t] >= mine) continue;
+                        const int32_t n = (int32_t)atomicAdd(&ctr[kTeamCtr + t], 1u);
+                        if (n < mine) got = ((n / kGroupItems) * kTeams + t) * kGroupItems + n % kGroupItems;
                     }
-                    if (mine <= 0 || (int32_t)seen[t] >= mine) continue;
-                    const int32_t n = (int32_t)atomicAdd(&ctr[kTeamCtr + t], 1u);
-                    if (n < mine) got = ((n / kGroupItems) * kTeams + t) * kGroupItems + n % kGroupItems;
+                }
+                if (got < 0) {                  // the groups are done (or there are none): the list
+                    const int32_t n = plan.team_items + (int32_t)atomicAdd(&ctr[0], 1u);
+                    got = n < plan.n_items ? n : -1;
+                    if (groups_left) got |= (int32_t)0x40000000;        // tells the others: no groups left
                 }
                 s_item = got;
             }
             __syncthreads();
-            const int32_t id = __builtin_amdgcn_readfirstlane(s_item);
-            if (id < 0) break;
-            run_item<T, TRI>(plan, id, m, reinterpret_cast<T*>(smem), sp);
+            id = __builtin_amdgcn_readfirstlane(s_item);
+            if (id >= 0 && (id & 0x40000000)) {
+                groups_left = false;
+                id &= 0x3FFFFFFF;
+            } else if (id < 0) {
+                groups_left = false;
+            }
         }
-    }
-    for (;;) {
-        __syncthreads();                        // the previous block's LDS reads and s_item are done with
-        if (threadIdx.x == 0) s_item = (int32_t)atomicAdd(&ctr[0], 1u);
-        __syncthreads();
-        const int32_t id = plan.team_items + __builtin_amdgcn_readfirstlane(s_item);
-        if (id >= plan.n_items) break;
+        if (id < 0) break;
         run_item<T, TRI>(plan, id, m, reinterpret_cast<T*>(smem), sp);
     }
-    if (threadIdx.x == 0) {
+    if (persistent && threadIdx.x == 0) {
         __threadfence();
-        if (atomicAdd(&ctr[1], 1u) == gridDim.x - 1) {  // every workgroup has left its loops
+        if (atomicAdd(&ctr[1], 1u) == gridDim.x - 1) {  // every workgroup has left its loop
 #pragma unroll
             for (int c = 0; c < kLaunchCounters; ++c) ctr[c] = 0u;
             __threadfence();
@@ -897,14 +907,10 @@ hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, c
     m.alpha = (T)alpha;
     m.beta = (T)beta;
     m.lower = true;
-    if (!persistent) {
-        hipExtLaunchKernelGGL((tbs_syrk_kernel<T, NPASS, TRI>), dim3((unsigned)plan.n_items), dim3(kThreads), 0,
-                              stream, nullptr, lease.done, 0, plan, m, (T*)ws, lease.slice_ctr);
-        return hipGetLastError();
-    }
-    hipExtLaunchKernelGGL((tbs_syrk_persistent_kernel<T, NPASS, TRI>), dim3((unsigned)max_workgroups),
-                          dim3(kThreads), 0, stream, nullptr, lease.done, 0, plan, m, lease.ctr, (T*)ws,
-                          lease.slice_ctr);
+    // (one kernel for both forms: without counters, workgroup b runs item b)
+    hipExtLaunchKernelGGL((tbs_syrk_kernel<T, NPASS, TRI>), dim3((unsigned)(persistent ? max_workgroups : plan.n_items)),
+                          dim3(kThreads), 0, stream, nullptr, lease.done, 0, plan, m,
+                          persistent ? lease.ctr : (unsigned int*)nullptr, (T*)ws, lease.slice_ctr);
     return hipGetLastError();
 }
 
