@@ -182,8 +182,9 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
                                 tbs_plan_info* out);
 
 /* Expands the plan into its work list, with the very index arithmetic the kernels use.
- * Item t occupies items[t*10 .. t*10+9]:  [0] kind (0 triangle block, 1 rectangle, 2 diagonal tile,
- * 3 empty, 4 rectangle with diagonal tiles), [1] number of row-side tile rows, [2] number of
+ * Item t occupies items[t*13 .. t*13+12] (TBS_ENUMERATE_COLUMNS values):  [0] kind (0 triangle block,
+ * 1 rectangle, 2 diagonal tile, 3 empty, 4 rectangle with diagonal tiles, 5 augmented triangle block:
+ * see below), [1] number of row-side tile rows, [2] number of
  * column-side tile rows, [3..7] tile-row ids, -1 = unused (triangle block: the members of R in zone
  * order in [3..6]; rectangle: column side in [3..5], row side in [6..7]; diagonal tile: [3]).  A
  * rectangle updates the tiles (r, q) of its row x column product with q < r only; kind 4 also
@@ -191,8 +192,14 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
  * small N, on M (which sets how finely the tail of the list is cut so that all compute units finish
  * together).  [8], [9]: the item is part [8] of the [9] parts its block is cut into along the
  * contraction dimension (0 of 1: a whole block); the parts of a block are consecutive items.
+ * Kind 5: the triangle block on the four tile rows [3..6] plus two tiles of the diagonal zones, each
+ * between one of those rows and one further row of the same zone ([7] for the first, [10] for the
+ * second; -1 for other kinds): [11] = 6: tile ([7], [3]), 7: tile ([7], [4]); [12] = 8: tile ([10], [5]),
+ * 9: tile ([5], [10]), 10: tile ([10], [6]), 11: tile ([6], [10]) (row, column); where the two rows of a
+ * tile are equal it is a diagonal tile, updated on and below the diagonal.
  * `square` as for the query.  `capacity` counts items; *n_items receives the number the plan has
  * (call with items == NULL to size the buffer).  HOST pointers. */
+#define TBS_ENUMERATE_COLUMNS 13
 tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32_t square,
                                     int32_t* items, int64_t capacity, int64_t* n_items);
 

@@ -248,15 +248,19 @@ def tbs_syrk_lower_query(dtype_code, N, M, square=False) -> dict:
     return {name: getattr(info, name) for name, _ in PlanInfo._fields_}
 
 
+ENUMERATE_COLUMNS = 13          # TBS_ENUMERATE_COLUMNS of the header
+
+
 def tbs_syrk_lower_enumerate(dtype_code, N, M, square=False) -> np.ndarray:
-    """The work list as an (n_items, 10) int32 array: kind, nrow, ncol, five tile-row slots, part, parts.
+    """The work list as an (n_items, ENUMERATE_COLUMNS) int32 array: kind, nrow, ncol, five tile-row slots,
+    part, parts, and for augmented triangle blocks a sixth tile row and the codes of the two extra tiles.
     square: False/0 the plan used with a workspace, True/1 the square baseline, 2 the plan used without."""
     lib = load()
     n = ctypes.c_int64(0)
     st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(square), None, 0, ctypes.byref(n))
     if st != TBS_OK:
         raise TbsError(st, "tbs_syrk_lower_enumerate")
-    out = np.empty((n.value, 10), dtype=np.int32)
+    out = np.empty((n.value, ENUMERATE_COLUMNS), dtype=np.int32)
     st = lib.tbs_syrk_lower_enumerate(dtype_code, N, M, int(square), out.ctypes.data, n.value,
                                       ctypes.byref(n))
     if st != TBS_OK:

@@ -54,14 +54,21 @@ LDS_RING_BYTES = 144 * 1024     # ring of chunk buffers (the kernel's LDS alloca
 MAX_BUFS = 8
 
 SHAPES = {
-    "Tri": dict(a=[1, 2, 3], b=[0, 1, 2],
+    "Tri": dict(np=4, a=[1, 2, 3], b=[0, 1, 2],
                 slots=[(0, 0), (1, 0), (1, 1), (2, 0), (2, 1), (2, 2)], col_side=lambda p: False),
-    "Rect": dict(a=[3, 4], b=[0, 1, 2],
+    "Rect": dict(np=5, a=[3, 4], b=[0, 1, 2],
                  slots=[(0, 0), (0, 1), (0, 2), (1, 0), (1, 1), (1, 2)], col_side=lambda p: p < 3),
+    # a triangle block on panels 0..3 plus two tiles of the diagonal zones, each between a panel of the
+    # block and one further panel (4, 5): slots 6, 7 = panel 4 x panel 0 / 1; slots 8..11 = panel 5 x
+    # panel 2, panel 2 x panel 5, panel 5 x panel 3, panel 3 x panel 5 (one of each group per block)
+    "Aug": dict(np=6, a=[1, 2, 3, 4, 5], b=[0, 1, 2, 3, 5],
+                slots=[(0, 0), (1, 0), (1, 1), (2, 0), (2, 1), (2, 2),
+                       (3, 0), (3, 1), (4, 2), (1, 4), (4, 3), (2, 4)], col_side=lambda p: False),
 }
 # Rect: the full 2 x 3 block and its sub-rectangles, then the three sets a two-row block can be left with
 # when it straddles the diagonal (0x3B, 0x19, 0x08: the first row loses its last one or two tiles / is empty)
-FAST_SETS = {"Tri": [0x3F, 0x07, 0x01], "Rect": [0x3F, 0x1B, 0x09, 0x07, 0x03, 0x01, 0x3B, 0x19, 0x08]}
+FAST_SETS = {"Tri": [0x3F, 0x07, 0x01], "Rect": [0x3F, 0x1B, 0x09, 0x07, 0x03, 0x01, 0x3B, 0x19, 0x08],
+             "Aug": [0x3F | (1 << e1) | (1 << e2) for e1 in (6, 7) for e2 in (8, 9, 10, 11)]}
 
 TYPES = {
     "double": dict(ks=4, rd="ds_read_b64", mfma="v_mfma_f64_16x16x4_f64", opregs=2),
@@ -69,7 +76,7 @@ TYPES = {
 }
 
 TMP_BASE = 128                   # first vector register the loop uses as scratch (declared clobbered)
-PB = 86                          # scalar registers s[86:95]: the moving pointers of up to five panels
+PB = 86                          # scalar registers s[86:97]: the moving pointers of up to six panels
 
 
 def vreg(first, n):
@@ -203,7 +210,7 @@ def gen(ty, shape_name, slots_mask):
     fn = f"""
 // {ty}, {shape_name} block, slots 0x{slots_mask:02x}: panels {panels}, ring of {NBUF} chunk buffers of {CB} bytes,
 // {len(slots) * 4} MFMAs and {n_op} operand reads per k-step, {LPC} loads per wavefront and chunk
-__device__ __forceinline__ void {name}(Cfg<{ty}>::acc_t (&acc)[6][4], const AsmLoopArgs& g, const uint32_t (&go)[10])
+__device__ __forceinline__ void {name}(Cfg<{ty}>::acc_t (&acc)[{len(S["slots"])}][4], const AsmLoopArgs& g, const uint32_t (&go)[{2 * S["np"]}])
 {{
     uint32_t cnt, tmp;
     asm volatile(
@@ -232,8 +239,8 @@ def main():
     out.append("\ntemplate <typename T, class Shape, uint32_t SLOTS> struct AsmLoop;\n")
     for ty, shape_name, mask, name in table:
         out.append(f"template <> struct AsmLoop<{ty}, {shape_name}Shape, 0x{mask:02x}u> {{\n"
-                   f"    static __device__ __forceinline__ void run(Cfg<{ty}>::acc_t (&acc)[6][4], "
-                   f"const AsmLoopArgs& g, const uint32_t (&go)[10]) {{ {name}(acc, g, go); }}\n}};\n")
+                   f"    static __device__ __forceinline__ void run(Cfg<{ty}>::acc_t (&acc)[{len(SHAPES[shape_name]['slots'])}][4], "
+                   f"const AsmLoopArgs& g, const uint32_t (&go)[{2 * SHAPES[shape_name]['np']}]) {{ {name}(acc, g, go); }}\n}};\n")
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "syrk_asm_loops.inc")
     text = "".join(out)
     if not (os.path.exists(path) and open(path).read() == text):   # untouched when nothing changed

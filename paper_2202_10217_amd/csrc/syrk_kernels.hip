@@ -7,6 +7,8 @@
 //     the columns of A, KC columns per step).  Every staged panel is used as left operand
 //     (rows of the tile) and as right operand (columns of the tile): the symmetric reuse that
 //     Section 5.1 is about;
+//   * an augmented triangle block: the same plus two tiles of the diagonal zones, each between a row of
+//     the block and one further row (8 tiles, all 256 accumulator registers of a lane in fp64, 6 panels);
 //   * a rectangular block of at most 2 x 3 tiles (Algorithm 4's square-block part: the last l
 //     tile rows and the recursion base), 5 panels for 6 tiles;
 //   * a diagonal tile: one panel, only the 10 of 16 sub-tiles on or below the diagonal.
@@ -77,6 +79,7 @@ struct TriShape {                         // panels 0..3 = R in zone order
     static constexpr bool col_side(int) { return false; }   // SYRK only: one matrix
     static constexpr bool active(int i, int j) { return j <= i; }
     static constexpr int slot(int i, int j) { return i * (i + 1) / 2 + j; }
+    static constexpr bool may_be_diagonal(int) { return false; }     // (its tile rows are pairwise different)
 };
 struct RectShape {                        // panels 0..2 = column side, 3..4 = row side
     static constexpr int NP = 5, NA = 2, NB = 3, NSLOT = 6;
@@ -85,12 +88,34 @@ struct RectShape {                        // panels 0..2 = column side, 3..4 = r
     static constexpr bool col_side(int p) { return p < 3; }
     static constexpr bool active(int, int) { return true; }
     static constexpr int slot(int i, int j) { return i * 3 + j; }
+    static constexpr bool may_be_diagonal(int) { return true; }
+};
+
+struct AugShape {                         // panels 0..3 = R in zone order, 4 and 5 = the further rows
+    static constexpr int NP = 6, NA = 5, NB = 5, NSLOT = 12;
+    static constexpr int a_panel(int i) { return i + 1; }
+    static constexpr int b_panel(int j) { return j < 4 ? j : 5; }
+    static constexpr bool col_side(int) { return false; }
+    // slots 0..5: the triangle block; 6, 7: panel 4 x panel 0 / 1; 8..11: panel 5 x panel 2, panel 2 x
+    // panel 5, panel 5 x panel 3, panel 3 x panel 5 (a block has one slot of 6..7 and one of 8..11)
+    static constexpr int slot(int i, int j)
+    {
+        if (i < 3 && j < 3 && j <= i) return i * (i + 1) / 2 + j;
+        if (i == 3 && j < 2) return 6 + j;
+        if (i == 4 && j == 2) return 8;
+        if (i == 1 && j == 4) return 9;
+        if (i == 4 && j == 3) return 10;
+        if (i == 2 && j == 4) return 11;
+        return -1;
+    }
+    static constexpr bool active(int i, int j) { return slot(i, j) >= 0; }
+    static constexpr bool may_be_diagonal(int s) { return s == 6 || s == 7 || s == 8; }
 };
 
 // which slots / row-side panels / column-side panels / LDS panels a set of slots needs
 template <class Shape> constexpr bool slot_on(uint32_t slots, int i, int j)
 {
-    return Shape::active(i, j) && ((slots >> Shape::slot(i, j)) & 1u);
+    return Shape::active(i, j) && ((slots >> (Shape::slot(i, j) & 31)) & 1u);
 }
 template <class Shape> constexpr bool a_used(uint32_t slots, int i)
 {
@@ -284,7 +309,7 @@ __device__ __forceinline__ const P* to_scalar(const P* p)
 struct AsmLoopArgs {
     uint32_t ada[8];        // LDS byte address of the lane's row-side operand piece for k-step j
     uint32_t adb[8];        // same for the column side (includes the wavefront's 16-row group)
-    const void* gP[5];      // first element of each panel the block uses (tile row, first column), in panel order
+    const void* gP[6];      // first element of each panel the block uses (tile row, first column), in panel order
     uint32_t nch;           // chunks, >= 1
     uint32_t step;          // bytes per chunk along a row
     uint32_t m0base;        // LDS byte address of the wavefront's 1 KB slice in panel 0, half 0, buffer 0
@@ -329,6 +354,66 @@ __device__ __forceinline__ void store_strip(const MatsT& m, int row0, int col, i
         }
 }
 
+// The same for whole tiles on the fast path: the lane's 16 elements lie at byte offsets from the first
+// element of the wavefront's strip that are the same for every tile (64 rows of C span less than 4 GiB:
+// checked by the caller).  MAY_DIAG (a constant once the caller's loops are unrolled): the tile may be a diagonal tile (`diag`, run time), of
+// which only the elements on or below the diagonal are read and written.  Nothing here branches around
+// a load: the compiler waits for every outstanding memory operation, stores included, wherever a loaded
+// value is used behind a branch, which made the sixteen stores of such a strip wait for each other.  A
+// lane's element above the diagonal is replaced by the diagonal element of its column for the load (a
+// valid address; the value is not used); only the stores are predicated.
+template <typename T>
+struct StripOffsets {
+    uint32_t off[4][4];
+    uint32_t on_diagonal;               // the element (c, c) of the lane's column c
+    uint32_t on_or_below;               // bit 4 rb + g: the element is on or below the diagonal of a diagonal tile
+    __device__ __forceinline__ void init(int64_t ldc, int lane, int w)
+    {
+        on_or_below = 0;
+        const int c = w * 16 + (lane & 15);
+        on_diagonal = (uint32_t)(((int64_t)c * ldc + (lane & 15)) * (int64_t)sizeof(T));
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int row = rb * 16 + Cfg<T>::row_of(g, lane);
+                off[rb][g] = (uint32_t)(((int64_t)row * ldc + (lane & 15)) * (int64_t)sizeof(T));
+                if (c <= row) on_or_below |= 1u << (4 * rb + g);
+            }
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ void load_strip_fast(TileStrip<T>& old, const T* strip, const StripOffsets<T>& so,
+                                                const bool MAY_DIAG, bool diag)
+{
+    const char* base = reinterpret_cast<const char*>(strip);
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t o = so.off[rb][g];
+            if (MAY_DIAG) o = (!diag || ((so.on_or_below >> (4 * rb + g)) & 1u)) ? o : so.on_diagonal;
+            old.v[rb][g] = *reinterpret_cast<const T*>(base + o);
+        }
+}
+
+template <typename T>
+__device__ __forceinline__ void store_strip_fast(T* strip, const StripOffsets<T>& so, T alpha, T beta,
+                                                 const typename Cfg<T>::acc_t (&acc)[4], const TileStrip<T>& old,
+                                                 const bool MAY_DIAG, bool diag)
+{
+    char* base = reinterpret_cast<char*>(strip);
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            if (!MAY_DIAG || !diag || ((so.on_or_below >> (4 * rb + g)) & 1u)) {
+                const T v = alpha * acc[rb][g];
+                *reinterpret_cast<T*>(base + so.off[rb][g]) = (beta != T(0)) ? beta * old.v[rb][g] + v : v;
+            }
+}
+
 // ---- blocks cut along the contraction dimension -------------------------------------------------
 // A sliced block is computed by `slices` workgroups, each over its share of the columns of A.  Every
 // one writes its accumulators to its own place in the workspace (in register order: coalesced, no
@@ -368,7 +453,12 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
     static_assert(KS % 2 == 0, "operand double buffering assumes an even number of k-steps");
     typedef typename Cfg<T>::acc_t acc_t;
     typedef Operands<T, Shape, SLOTS> Ops;
-    const int tid = threadIdx.x;
+    // (the thread's index passes through an empty assembly statement: what is derived from it -- LDS and
+    // global offsets, a dozen or two registers -- is then computed inside each instance of this function,
+    // not once for all of them at the top of the kernel, where it would occupy registers across every
+    // assembly loop, the largest of which leaves the compiler 136 of them)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
@@ -377,10 +467,16 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
     for (int p = 0; p < NP; ++p) nrows[p] = Shape::col_side(p) ? m.nq : m.nr;
 
     acc_t acc[Shape::NSLOT][4];
+    {
+        // (a zero the compiler cannot see through: otherwise it keeps a vector of zeros in registers for
+        // the whole kernel, across every assembly loop)
+        T zero = T(0);
+        asm volatile("" : "+v"(zero));
 #pragma unroll
-    for (int s = 0; s < Shape::NSLOT; ++s)
+        for (int s = 0; s < Shape::NSLOT; ++s)
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) acc[s][rb] = acc_t{0, 0, 0, 0};
+            for (int rb = 0; rb < 4; ++rb) acc[s][rb] = acc_t{zero, zero, zero, zero};
+    }
 
     const int M = m.M;
     // one pass over the contraction dimension per operand pair; the accumulators carry over (the
@@ -434,7 +530,7 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
         g.nch = (uint32_t)(M / KC);                         // whole chunks; the rest follows below
         g.step = to_scalar((uint32_t)(KC * ES * ks[Shape::b_panel(0)]));   // (all operands of a launch advance alike)
         g.m0base = lds0 + (uint32_t)w * 1024;
-        uint32_t go[10];
+        uint32_t go[2 * NP];
         int q = 0, np_used = 0;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
@@ -530,13 +626,15 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
         __syncthreads();
         if (*sc.flag == 0) return;                          // not the last part of this block
         __threadfence();
+        T zero = T(0);
+        asm volatile("" : "+v"(zero));                      // (as above: no vector of zeros kept for the whole kernel)
 #pragma unroll
         for (int s = 0; s < NS; ++s)
             if (FAST ? ((SLOTS >> s) & 1u) != 0 : ((pmask >> s) & 1u) != 0) {
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) acc[s][rb][g] = T(0);
+                    for (int g = 0; g < 4; ++g) acc[s][rb][g] = zero;
                 // two parts are requested together (32 loads in flight per lane), then added in order
                 for (int sl0 = 0; sl0 < sc.slices; sl0 += 2) {
                     T v[2][16];
@@ -562,33 +660,48 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
 
     // Epilogue.
     const int col16 = w * 16 + (lane & 15);
-    if (FAST && !ragged) {
-        // the old values of three tiles are requested at once (the operand registers of the loop are
-        // free now), then their strips are computed and stored
+    if (FAST && !ragged && (int64_t)kTile * m.ldc * (int64_t)sizeof(T) < ((int64_t)1 << 32)) {
+        // the old values of EG tiles are requested at once (the operand registers of the loop are free
+        // now), then their strips are computed and stored.  Tiles are taken in the order of their slots;
+        // EG is what fits the registers: all tiles in fp32 (at most 128 registers of values), up to four
+        // in fp64, plus the 16 offsets.
         const bool rd = m.beta != T(0);
+        constexpr int NT = __builtin_popcount(SLOTS);
+        constexpr int EG = (sizeof(T) == 4 || NT <= 4) ? NT : (NT + 1) / 2;
+        StripOffsets<T> so;
+        so.init(m.ldc, lane, w);
 #pragma unroll
-        for (int s0 = 0; s0 < Shape::NSLOT; s0 += 3) {      // three tiles' old values in flight at a time
-            TileStrip<T> old[3];
-#pragma unroll
-            for (int i = 0; i < Shape::NA; ++i)
-#pragma unroll
-                for (int j = 0; j < Shape::NB; ++j) {
-                    const int sl = Shape::slot(i, j);
-                    if (slot_on<Shape>(SLOTS, i, j) && sl >= s0 && sl < s0 + 3 && rd)
-                        old[sl - s0].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
-                                                          prow[Shape::b_panel(j)] * kTile + col16, lane,
-                                                          ((dmask >> sl) & 1u) != 0);
-                }
+        for (int t0 = 0; t0 < NT; t0 += EG) {
+            TileStrip<T> old[EG];
 #pragma unroll
             for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
-                for (int j = 0; j < Shape::NB; ++j) {
-                    const int sl = Shape::slot(i, j);
-                    if (slot_on<Shape>(SLOTS, i, j) && sl >= s0 && sl < s0 + 3)
-                        store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
-                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[sl], old[sl - s0],
-                                              ((dmask >> sl) & 1u) != 0);
-                }
+                for (int j = 0; j < Shape::NB; ++j)
+                    if (slot_on<Shape>(SLOTS, i, j)) {
+                        const int sl = Shape::slot(i, j);
+                        const int d = __builtin_popcount(SLOTS & ((1u << sl) - 1u));    // place among the block's tiles
+                        if (d >= t0 && d < t0 + EG && rd)
+                            load_strip_fast(old[d - t0],
+                                            m.C + (int64_t)prow[Shape::a_panel(i)] * kTile * m.ldc +
+                                                prow[Shape::b_panel(j)] * kTile + w * 16,
+                                            so, Shape::may_be_diagonal(sl), ((dmask >> sl) & 1u) != 0);
+                    }
+            // every old value has arrived before the first (predicated) store: s_waitcnt vmcnt(0), told to
+            // the compiler so that it places no waits of its own between the stores
+            if (rd) __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+            for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+                for (int j = 0; j < Shape::NB; ++j)
+                    if (slot_on<Shape>(SLOTS, i, j)) {
+                        const int sl = Shape::slot(i, j);
+                        const int d = __builtin_popcount(SLOTS & ((1u << sl) - 1u));
+                        if (d >= t0 && d < t0 + EG)
+                            store_strip_fast(m.C + (int64_t)prow[Shape::a_panel(i)] * kTile * m.ldc +
+                                                 prow[Shape::b_panel(j)] * kTile + w * 16,
+                                             so, m.alpha, m.beta, acc[sl], old[d - t0], Shape::may_be_diagonal(sl),
+                                             ((dmask >> sl) & 1u) != 0);
+                    }
         }
     } else {
 #pragma unroll
@@ -626,6 +739,11 @@ template <> struct FastSets<RectShape> {
     }
 };
 
+template <> struct FastSets<AugShape> {
+    static constexpr int N = 8;
+    static constexpr uint32_t set(int n) { return 0x3Fu | (1u << (6 + (n >> 2))) | (1u << (8 + (n & 3))); }
+};
+
 template <typename T, class Shape, int IDX, bool CAN_SLICE, class MatsT>
 __device__ __forceinline__ bool try_fast(const MatsT& m, const int (&prow)[Shape::NP], uint32_t pmask,
                                          uint32_t dmask, T* lds, const SliceCtx<T>& sc)
@@ -652,6 +770,29 @@ __device__ __forceinline__ bool try_fast(const MatsT& m, const int (&prow)[Shape
     }
 }
 
+// Whether the operands of a launch suit the assembly loops.
+template <typename T, class MatsT>
+__device__ __forceinline__ bool fast_path_ok(const MatsT& m)
+{
+    constexpr int KC = Cfg<T>::KC;
+    // the assembly loop addresses a panel's 64 rows with 32-bit byte offsets from the panel's start
+    const int64_t lim = (int64_t)1 << 32;
+    // (rows need no alignment beyond that of an element: the loads into LDS take 16 bytes from any
+    // element-aligned address, at full speed)
+    // (column panels: the KC memory rows of a chunk instead, and whole 16-byte pieces inside the matrix)
+    bool fast_ok = m.M >= KC;
+#pragma unroll
+    for (int pass = 0; pass < MatsT::NPASS; ++pass) {
+        const Side<T>&r = m.R[pass], &q = m.Q[pass];
+        const bool colp = r.ks != 1;
+        fast_ok = fast_ok && (q.ks != 1) == colp;
+        fast_ok = fast_ok && (colp ? KC * r.ks + kTile : kTile * r.rs) * (int64_t)sizeof(T) < lim &&
+                  (colp ? KC * q.ks + kTile : kTile * q.rs) * (int64_t)sizeof(T) < lim;
+        if (colp) fast_ok = fast_ok && r.rs == 1 && q.rs == 1 && m.nr % Cfg<T>::VEC == 0 && m.nq % Cfg<T>::VEC == 0;
+    }
+    return fast_ok;
+}
+
 // with_diag: tiles (r, r) belong to the block (their part on and below the diagonal)
 template <typename T, class Shape, bool CAN_SLICE = true, class MatsT>
 __device__ __forceinline__ void run_block(const Item& it, const MatsT& m, T* lds, const SliceCtx<T>& sc,
@@ -675,24 +816,23 @@ __device__ __forceinline__ void run_block(const Item& it, const MatsT& m, T* lds
                 }
             }
         }
-    constexpr int KC = Cfg<T>::KC;
-    // the assembly loop addresses a panel's 64 rows with 32-bit byte offsets from the panel's start
-    const int64_t lim = (int64_t)1 << 32;
-    // (rows need no alignment beyond that of an element: the loads into LDS take 16 bytes from any
-    // element-aligned address, at full speed)
-    // (column panels: the KC memory rows of a chunk instead, and whole 16-byte pieces inside the matrix)
-    bool fast_ok = m.M >= KC;
-#pragma unroll
-    for (int pass = 0; pass < MatsT::NPASS; ++pass) {
-        const Side<T>&r = m.R[pass], &q = m.Q[pass];
-        const bool colp = r.ks != 1;
-        fast_ok = fast_ok && (q.ks != 1) == colp;
-        fast_ok = fast_ok && (colp ? KC * r.ks + kTile : kTile * r.rs) * (int64_t)sizeof(T) < lim &&
-                  (colp ? KC * q.ks + kTile : kTile * q.rs) * (int64_t)sizeof(T) < lim;
-        if (colp) fast_ok = fast_ok && r.rs == 1 && q.rs == 1 && m.nr % Cfg<T>::VEC == 0 && m.nq % Cfg<T>::VEC == 0;
-    }
-    if (fast_ok && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
+    if (fast_path_ok<T>(m) && try_fast<T, Shape, 0, CAN_SLICE>(m, prow, pmask, dmask, lds, sc)) return;
     block_body<T, Shape, (1u << Shape::NSLOT) - 1, false, CAN_SLICE>(m, prow, pmask, dmask, lds, sc, true);
+}
+
+// An augmented triangle block.  There is no general path for eight tiles: plans with such blocks are
+// used only where fast_path_ok holds (the host checks the same conditions before it chooses the plan).
+template <typename T, class MatsT>
+__device__ __forceinline__ void run_aug_block(const Item& it, const MatsT& m, T* lds)
+{
+    int prow[AugShape::NP];
+#pragma unroll
+    for (int p = 0; p < AugShape::NP; ++p) prow[p] = it.rows[p];
+    const uint32_t pmask = 0x3Fu | (1u << it.aug1) | (1u << it.aug2);
+    uint32_t dmask = 0;
+    if (it.rows[4] == ((it.aug1 == 6) ? it.rows[0] : it.rows[1])) dmask |= 1u << it.aug1;
+    if (it.aug2 == 8 && it.rows[5] == it.rows[2]) dmask |= 1u << 8;
+    try_fast<T, AugShape, 0, false>(m, prow, pmask, dmask, lds, SliceCtx<T>{});
 }
 
 // ---- the kernels: workgroup -> block(s) -> code path ------------------------------------------
@@ -730,17 +870,19 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
         sc.slices = it.slices;
         sc.slice = it.slice;
     }
-    if (it.kind == kTri) {
-        if constexpr (TRI) run_block<T, TriShape>(it, m, lds, sc);      // (plans of rectangles have none)
-    } else if (it.kind == kRect) {
-        run_block<T, RectShape>(it, m, lds, sc);
-    } else if (it.kind == kRectDiag) {
-        run_block<T, RectShape>(it, m, lds, sc, true);
-    } else if (it.kind == kDiag) {                          // a 1 x 1 rectangle on the diagonal
-        Item d = it;
-        d.rows[0] = it.rows[0];
-        d.rows[kRectCols] = it.rows[0];
-        run_block<T, RectShape>(d, m, lds, sc, true);
+    // (one call site per shape: each is a copy of that shape's code)
+    Item x = it;
+    if (x.kind == kDiag) {                                  // a 1 x 1 rectangle on the diagonal
+        x.rows[kRectCols] = x.rows[0];
+        x.kind = kRectDiag;
+    }
+    if (x.kind == kTri) {
+        if constexpr (TRI) run_block<T, TriShape>(x, m, lds, sc);       // (plans of rectangles have none)
+    } else if (x.kind == kAug) {
+        // (the host hands out augmented plans only for operands that suit the assembly loops)
+        if constexpr (TRI) run_aug_block<T>(x, m, lds);
+    } else if (x.kind == kRect || x.kind == kRectDiag) {
+        run_block<T, RectShape>(x, m, lds, sc, x.kind == kRectDiag);
     }
 }
 

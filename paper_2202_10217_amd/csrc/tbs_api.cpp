@@ -44,8 +44,10 @@ int32_t compute_units()
 // The environment variables that change what the planner builds (all optional, for measurements).
 // They are read at every call and are part of the cache key, so a plan built under one setting is
 // never handed out under another.
+constexpr bool kAugmentByDefault = true;
+
 struct PlanEnv {
-    std::string costs, family, slices, tuning, groups;
+    std::string costs, family, slices, tuning, groups, augment;
     static PlanEnv read()
     {
         auto get = [](const char* name) {
@@ -53,7 +55,7 @@ struct PlanEnv {
             return std::string(v ? v : "");
         };
         return PlanEnv{get("TBS_PLAN_COSTS"), get("TBS_PLAN_FAMILY"), get("TBS_SYRK_SLICES"), get("TBS_PLAN_TUNING"),
-                       get("TBS_SYRK_DIE_GROUPS")};
+                       get("TBS_SYRK_DIE_GROUPS"), get("TBS_SYRK_AUGMENT")};
     }
 };
 
@@ -61,19 +63,21 @@ struct PlanEnv {
 // compared with the fixed cost of a block (prologue, epilogue, dispatch: about 20 us against
 // M * 2 * 64 * 64 flops at one compute unit's share of the MFMA peak), which decides how finely the
 // tail of the work list is cut.  M enters through its power-of-two bucket.  Built once, kept.
-const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M, bool sliced)
+// allow_aug = false: no augmented blocks (they have no general path: the caller passes false for operands
+// that do not suit the assembly loops, see operands_suit_fast_path).
+const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M, bool sliced, bool allow_aug = true)
 {
     static std::mutex mu;
-    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool, std::string, std::string, std::string, std::string,
-                               std::string>,
+    static std::map<std::tuple<int32_t, bool, int32_t, int32_t, bool, bool, std::string, std::string, std::string,
+                               std::string, std::string, std::string>,
                     tbs::Plan>
         cache;
     int32_t bucket = 0;
     while (bucket < 30 && ((int64_t)3 << bucket) / 2 <= M) ++bucket;     // M ~ 2^bucket
     const PlanEnv env = PlanEnv::read();
     std::lock_guard<std::mutex> lock(mu);
-    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket, sliced, env.costs, env.family, env.slices,
-                               square ? std::string() : env.tuning, env.groups);
+    auto key = std::make_tuple(T, square, (int32_t)dtype, bucket, sliced, allow_aug, env.costs, env.family, env.slices,
+                               square ? std::string() : env.tuning, env.groups, env.augment);
     auto it = cache.find(key);
     if (it == cache.end()) {
         const double tile_us = (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 0.01334 : 0.02668);
@@ -102,6 +106,17 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
         const double a_bytes = (double)T * kTile * (double)((int64_t)1 << bucket) * (dtype == TBS_F32 ? 4.0 : 8.0);
         bool die_groups = a_bytes > 192.0 * 1048576.0;
         if (!env.groups.empty()) die_groups = env.groups[0] != '0';
+        // Top-level triangle blocks that take two tiles of the diagonal zones with them (eight tiles per
+        // block instead of six: the fixed cost of a block is spread over a third more work, and the zones
+        // need no blocks of their own).  TBS_SYRK_AUGMENT=1 / 0 lets the planner consider them or not.
+        // By default in fp64 with tiles that take at least 2.5 times a block's fixed cost (M of about 2000
+        // and more), and there only where a compute unit gets at most two top-level blocks (the planner's
+        // rule): measured +1.4 to +4 % for N = 4096 .. 5632; with shorter tiles or in fp32 the larger
+        // epilogue eats the gain (-4 to +1 %).
+        bool augment = kAugmentByDefault && dtype == TBS_F64 && block_us <= 0.4 * tile_us;
+        if (!env.augment.empty()) augment = env.augment[0] != '0';
+        // (the smallest M of the bucket must give the assembly loops a whole chunk)
+        if (!allow_aug || ((int64_t)3 << bucket) / 4 < (dtype == TBS_F32 ? 32 : 16)) augment = false;
         // blocks may be cut along the contraction dimension while a part keeps at least 8 chunks of
         // the smallest M of the bucket; TBS_SYRK_SLICES=0 turns that off, "levels,rows,...,tri,rect,
         // tail_blocks,tail" in TBS_PLAN_TUNING pins it
@@ -109,23 +124,24 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
         const int64_t m_low = ((int64_t)3 << bucket) / 4;
         int32_t max_slices = (int32_t)std::min<int64_t>(tbs::kMaxSlices, m_low / (8 * kc));
         if (!sliced || square || (!env.slices.empty() && env.slices[0] == '0')) max_slices = 1;
-        // TBS_PLAN_TUNING="levels,rows,cols,base,zone_rows,zone_cols[,tri,rect,tail_blocks,tail]" pins
+        // TBS_PLAN_TUNING="levels,rows,cols,base,zone_rows,zone_cols[,tri,rect,tail_blocks,tail[,augment]]" pins
         // the tuning the planner would otherwise choose (every tuning covers each tile exactly once)
         const char* pin = (square || env.tuning.empty()) ? nullptr : env.tuning.c_str();
-        int lv = 0, mr = 0, nc = 0, base = 0, mrd = 0, ncd = 0, st = 1, sr = 1, tb = 0, ts = 1;
-        if (pin && std::sscanf(pin, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &lv, &mr, &nc, &base, &mrd, &ncd, &st, &sr, &tb,
-                               &ts) >= 4 &&
+        int lv = 0, mr = 0, nc = 0, base = 0, mrd = 0, ncd = 0, st = 1, sr = 1, tb = 0, ts = 1, ag = 0;
+        if (pin && std::sscanf(pin, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &lv, &mr, &nc, &base, &mrd, &ncd, &st, &sr, &tb,
+                               &ts, &ag) >= 4 &&
             lv >= 0 && lv <= tbs::kMaxLevels && mr >= 1 && mr <= tbs::kRectRows && nc >= 1 && nc <= tbs::kRectCols) {
             tbs::PlanTuning tune{lv, mr, nc, base != 0, mrd, ncd};
             tune.xor_family = xor_family;
             tune.die_groups = die_groups;
+            tune.augment = ag != 0 && allow_aug;
             if (!tbs::build_plan(T, tune, &p)) return nullptr;
             if (max_slices > 1 && (st > 1 || sr > 1 || (tb > 0 && ts > 1))) {
                 tbs::Plan q;
                 if (tbs::apply_slicing(p, tbs::Slicing{st, sr, tb, ts}, &q)) p = q;
             }
         } else if (!tbs::choose_plan(T, square, compute_units(), overhead_tiles, &p, xor_family, max_slices,
-                                     slice_us / tile_us, per_part_us / tile_us, die_groups)) {
+                                     slice_us / tile_us, per_part_us / tile_us, die_groups, augment)) {
             return nullptr;
         }
         it = cache.emplace(key, p).first;
@@ -161,18 +177,30 @@ int persistent_workgroups(int reserve_units)
     return persistent ? std::max(1, compute_units() - std::max(reserve_units, env_reserve)) : 0;
 }
 
+// The conditions under which the kernels take the assembly loops (fast_path_ok in syrk_kernels.hip), on
+// the host: at least one whole chunk of columns; 64 panel rows (row panels) or one chunk of memory rows
+// (column panels) within 4 GiB; column panels: whole 16-byte pieces inside the matrix.
+bool operands_suit_fast_path(tbs_dtype dtype, int64_t n_rows, int64_t M, int64_t row_stride, int64_t k_stride)
+{
+    const int64_t es = dtype == TBS_F32 ? 4 : 8, kc = dtype == TBS_F32 ? 32 : 16, vec = 16 / es;
+    const int64_t lim = (int64_t)1 << 32;
+    if (M < kc) return false;
+    if (k_stride == 1) return kTile * row_stride * es < lim;
+    return row_stride == 1 && (kc * k_stride + kTile) * es < lim && n_rows % vec == 0;
+}
+
 // The plan a call uses: the one with cut blocks if the caller gave a workspace (which must then hold
 // its parts), else the one without.
 tbs_status plan_for_call(int32_t T, bool square, tbs_dtype dtype, int64_t M, const void* workspace,
-                         size_t workspace_bytes, const tbs::Plan** out)
+                         size_t workspace_bytes, const tbs::Plan** out, bool allow_aug)
 {
     const size_t es = dtype == TBS_F32 ? 4 : 8;
     *out = nullptr;
     if (workspace == nullptr || square) {
-        *out = cached_plan(T, square, dtype, M, false);
+        *out = cached_plan(T, square, dtype, M, false, allow_aug);
         return *out ? TBS_OK : TBS_EINVAL;
     }
-    const tbs::Plan* sliced = cached_plan(T, square, dtype, M, true);
+    const tbs::Plan* sliced = cached_plan(T, square, dtype, M, true, allow_aug);
     if (!sliced) return TBS_EINVAL;
     if (sliced->n_ws_blocks > 0) {
         if (workspace_bytes < tbs::syrk_workspace_bytes(dtype == TBS_F32, *sliced)) return TBS_EWORKSPACE;
@@ -189,7 +217,8 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
     const tbs::Plan* plan = nullptr;
-    const tbs_status ps = plan_for_call(T, square, dtype, M, workspace, workspace_bytes, &plan);
+    const bool aug_ok = operands_suit_fast_path(dtype, N, M, lda, 1);
+    const tbs_status ps = plan_for_call(T, square, dtype, M, workspace, workspace_bytes, &plan, aug_ok);
     if (ps != TBS_OK) return ps;
     int wgs = persistent_workgroups(reserve_units);
     tbs::CounterLease lease;
@@ -198,7 +227,7 @@ tbs_status syrk_impl(bool square, tbs_dtype dtype, int64_t N, int64_t M, double 
         if (!lease.ctr) {
             // every set of counters belongs to a launch on another stream that may still be running:
             // the form that needs none (one workgroup per block, no cut blocks)
-            plan = cached_plan(T, square, dtype, M, false);
+            plan = cached_plan(T, square, dtype, M, false, aug_ok);
             if (!plan) return TBS_EINVAL;
             wgs = 0;
         }
@@ -507,9 +536,13 @@ tbs_status tbs_syrk_lower_workspace(tbs_dtype dtype, int64_t N, int64_t M, size_
     *bytes = 0;
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
+    // (operands that do not suit the assembly loops get the plan without augmented blocks, which may cut
+    // other blocks: the figure covers both)
     const tbs::Plan* plan = cached_plan(T, false, dtype, M, true);
-    if (!plan) return TBS_EINVAL;
-    *bytes = tbs::syrk_workspace_bytes(dtype == TBS_F32, *plan);
+    const tbs::Plan* plain = cached_plan(T, false, dtype, M, true, false);
+    if (!plan || !plain) return TBS_EINVAL;
+    *bytes = std::max(tbs::syrk_workspace_bytes(dtype == TBS_F32, *plan),
+                      tbs::syrk_workspace_bytes(dtype == TBS_F32, *plain));
     return TBS_OK;
 }
 
@@ -599,14 +632,15 @@ tbs_status tbs_gram_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha, c
     const int32_t T = (int32_t)((M + kTile - 1) / kTile);
     hipStream_t stream = (hipStream_t)hip_stream;
     const tbs::Plan* plan = nullptr;
-    const tbs_status ps = plan_for_call(T, false, dtype, N, workspace, workspace_bytes, &plan);
+    const bool aug_ok = operands_suit_fast_path(dtype, M, N, 1, lda);
+    const tbs_status ps = plan_for_call(T, false, dtype, N, workspace, workspace_bytes, &plan, aug_ok);
     if (ps != TBS_OK) return ps;
     int wgs = persistent_workgroups(0);
     tbs::CounterLease lease;
     if ((wgs > 0 && plan->n_items > wgs) || plan->n_ws_blocks > 0) {
         if (tbs::acquire_counters(stream, &lease) != hipSuccess) return TBS_EHIP;
         if (!lease.ctr) {
-            plan = cached_plan(T, false, dtype, N, false);
+            plan = cached_plan(T, false, dtype, N, false, aug_ok);
             if (!plan) return TBS_EINVAL;
             wgs = 0;
         }
@@ -679,13 +713,16 @@ tbs_status tbs_syrk_lower_enumerate(tbs_dtype dtype, int64_t N, int64_t M, int32
     for (int32_t t = 0; t < plan->n_items; ++t) {
         tbs::Item it;
         tbs::tbs_decode(*plan, t, it);
-        int32_t* o = items + (int64_t)t * 10;
+        int32_t* o = items + (int64_t)t * TBS_ENUMERATE_COLUMNS;
         o[0] = it.kind;
         o[1] = it.nrow;
         o[2] = it.ncol;
         for (int s = 0; s < 5; ++s) o[3 + s] = it.rows[s];
         o[8] = it.slice;
         o[9] = it.slices;
+        o[10] = it.rows[5];
+        o[11] = it.aug1;
+        o[12] = it.aug2;
     }
     return TBS_OK;
 }

@@ -16,6 +16,20 @@
 //   (item kind kRectDiag); a plan whose base zones are triangle blocks lists all diagonal tiles
 //   separately instead (kDiag).
 //
+// Augmented plans (a choice of this library, not of the paper: a compute unit has accumulators for eight
+// tiles, a triangle block on k = 4 tile rows has six): the top-level triangle blocks each take two tiles
+// of the diagonal zones with them, a tile between one of the block's rows and one further row of the
+// same zone.  The c^2 blocks absorb every off-diagonal tile of the k zones (2 c^2 - 2 c of them) and the
+// diagonal tiles of zones 0 and 2, so there is no recursion: what is left are the diagonal tiles of
+// zones 1 and 3 and the last l tile rows.  Which tile goes to which block, for block (i, j):
+//   zones 0 and 1 (f(0) = j, f(1) = i):  i > j: tile (i, j) of zone 0;  j > i: tile (j, i) of zone 1;
+//     i = j: the diagonal tile (j, j) of zone 0.  Every off-diagonal tile of the two zones exactly once.
+//   zones 2 and 3:  j = 0: the diagonal tile of zone 2 on the block's row.  Otherwise a tile {f, f + j}
+//     (cyclic family: + modulo c, zone 2 for j < c / 2, zone 3 for j > c / 2, c is odd) or {f, f XOR j}
+//     (XOR family: zone 2 if i has the highest bit of j, else zone 3), f the block's row in that zone:
+//     for a fixed j the blocks that use a zone give pairwise different pairs whose difference is j,
+//     and every pair of rows of a zone has exactly one j (cyclic: one of +-j) that leads to it.
+//
 // The descriptor is small enough to be a kernel argument; every workgroup turns its index into
 // its block with tbs_decode().  The host uses the same function to expand, count and check plans,
 // so what is tested on the CPU is what the kernels execute.
@@ -36,18 +50,20 @@ constexpr int kMaxLevels = 10;
 constexpr int kMaxSegs = 28;
 constexpr int kRectRows = 2;     // rectangular block: at most 2 x 3 tiles
 constexpr int kRectCols = 3;
-constexpr int kMaxPanels = 5;    // panels of A a block can stage (k, or kRectRows + kRectCols)
+constexpr int kMaxPanels = 6;    // panels of A a block can stage (k + 2, or kRectRows + kRectCols)
 constexpr int kGroupItems = 32;  // blocks of a group that the workgroups of one die take together
 
 // kRect: tiles (r, q) of the block's rows x columns with q < r.  kRectDiag: q <= r, where of a tile
 // (r, r) only the part on and below the diagonal belongs to the block.
-enum ItemKind : int32_t { kTri = 0, kRect = 1, kDiag = 2, kEmpty = 3, kRectDiag = 4 };
+// kAug: a triangle block on rows[0..3] plus the tiles named by aug1 and aug2 (see Item).
+enum ItemKind : int32_t { kTri = 0, kRect = 1, kDiag = 2, kEmpty = 3, kRectDiag = 4, kAug = 5 };
 
 enum SegKind : int32_t {
     kSegTri = 0,       // c^2 triangle blocks in each zone of a level
     kSegTriBase = 1,   // one triangle block on the consecutive rows of each base zone
     kSegRect = 2,      // grid of rectangular blocks inside each zone of a level
-    kSegDiag = 3       // all diagonal tiles (only in plans whose rectangles do not carry them)
+    kSegDiag = 3,      // all diagonal tiles (only in plans whose rectangles do not carry them)
+    kSegDiagRun = 4    // the diagonal tiles of the tile rows [r0, r1) (augmented plans)
 };
 
 struct Seg {
@@ -72,6 +88,8 @@ struct Seg {
     // bits form a subspace that contains {0, 1, x, x + 1} and x times it): a group is a triangle block
     // one level up in the sense of Section 5.1, for a fast memory shared by 32 compute units.
     int32_t group;
+    // kSegTri, level 0: every block takes two tiles of the diagonal zones with it (item kind kAug)
+    int32_t aug;
 };
 
 struct Plan {
@@ -94,7 +112,12 @@ struct Item {
     int32_t ncol;               // rectangle: column-side tile rows; otherwise 0
     // tile rows, -1 = unused.  Triangle block: R in zone order in slots 0..k-1.  Rectangle: column
     // side in slots 0..2, row side in slots 3..4.  Diagonal tile: slot 0.
+    // Augmented triangle block: slots 4 and 5 are the further rows of its two extra tiles.
     int32_t rows[kMaxPanels];
+    // kAug: which tiles the extra panels form.  aug1 = 6: (rows[4], rows[0]), 7: (rows[4], rows[1]);
+    // aug2 = 8: (rows[5], rows[2]), 9: (rows[2], rows[5]), 10: (rows[5], rows[3]), 11: (rows[3], rows[5])
+    // (row, column of the tile; equal rows: the diagonal tile, of which the lower part belongs to the block).
+    int32_t aug1, aug2;
     int32_t slice, slices;      // this item is part `slice` of `slices` of its block (0 of 1: the whole block)
     int32_t ws_block;           // sliced blocks: which stretch of the workspace
 };
@@ -118,6 +141,7 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
     it.slice = 0;
     it.slices = 1;
     it.ws_block = -1;
+    it.aug1 = it.aug2 = 0;
     for (int s = 0; s < kMaxPanels; ++s) it.rows[s] = -1;
     int32_t si = 0;
     while (si + 1 < p.nseg && id >= p.seg[si + 1].first) ++si;
@@ -160,6 +184,38 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
             it.rows[2] = base + 2 * c + (i ^ j);
             it.rows[3] = base + 3 * c + (i ^ xj);
         }
+        if (sg.aug) {
+            it.kind = kAug;
+            if (i >= j) {                           // i = j: the diagonal tile of zone 0 (rows[4] = rows[0])
+                it.rows[4] = base + i;
+                it.aug1 = 6;
+            } else {
+                it.rows[4] = base + c + j;
+                it.aug1 = 7;
+            }
+            int32_t zone = 2;                       // j = 0: the diagonal tile of zone 2 (rows[5] = rows[2])
+            if (j != 0) {
+                if (m == 0) {
+                    zone = (2 * j < c) ? 2 : 3;
+                } else {
+                    int32_t hb = 0;
+                    while ((j >> (hb + 1)) != 0) ++hb;
+                    zone = ((i >> hb) & 1) ? 2 : 3;
+                }
+            }
+            const int32_t f = ((zone == 2) ? it.rows[2] : it.rows[3]) - base - zone * c;   // (no indexing by a variable)
+            int32_t other = f;
+            if (j != 0) {
+                if (m == 0) {
+                    other = f + j;
+                    if (other >= c) other -= c;
+                } else {
+                    other = f ^ j;
+                }
+            }
+            it.rows[5] = base + zone * c + other;
+            it.aug2 = (zone == 2) ? (other >= f ? 8 : 9) : (other > f ? 10 : 11);
+        }
     } else if (sg.kind == kSegTriBase) {
         const int32_t base = zone_base(p, sg.level, t);
         it.kind = kTri;
@@ -184,6 +240,10 @@ TBS_HD void tbs_decode(const Plan& p, int32_t id, Item& it)
             if (q < it.ncol) it.rows[q] = base + ca + q;
         for (int32_t r = 0; r < kRectRows; ++r)
             if (r < it.nrow) it.rows[kRectCols + r] = base + ra + r;
+    } else if (sg.kind == kSegDiagRun) {
+        it.kind = kDiag;
+        it.nrow = 1;
+        it.rows[0] = sg.r0 + t;
     } else {
         it.kind = kDiag;
         it.nrow = 1;

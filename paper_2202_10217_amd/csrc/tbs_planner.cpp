@@ -51,6 +51,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
     const int32_t k = p.k;
     // rectangles that cover a triangular region take its diagonal tiles along, unless base zones are
     // triangle blocks (which cannot): then every diagonal tile is an item of its own
+    if (tune.augment && tune.tri_base) return false;        // (augmented blocks take diagonal tiles themselves)
     const bool with_diag = !tune.tri_base;
     {
         int32_t level = 0, Tl = T;
@@ -95,12 +96,25 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
             s.level = level;
             s.count = (int32_t)(nz * c * c);
             s.group = (tune.die_groups && level == 0 && fam >= 3) ? 1 : 0;
+            s.aug = (tune.augment && level == 0) ? 1 : 0;
             tri.push_back(s);
             const int32_t done = k * c, l = Tl - done;
             if (l > 0) {                                    // the last l tile rows
                 rect.push_back(rect_seg(level, nz, done, Tl, 0, done, mr, nc));
                 if (l >= (with_diag ? 1 : 2))
                     rect.push_back(rect_seg(level, nz, done, Tl, done, with_diag ? Tl : Tl - 1, mrt, nct, with_diag));
+            }
+            if (s.aug) {
+                // the blocks have taken every tile of the zones except the diagonal tiles of zones 1 and 3
+                for (int32_t z = 1; z < k; z += 2) {
+                    Seg d{};
+                    d.kind = kSegDiagRun;
+                    d.r0 = z * c;
+                    d.r1 = (z + 1) * c;
+                    d.count = c;
+                    rect.push_back(d);
+                }
+                break;
             }
             nz *= k;
             Tl = c;
@@ -123,7 +137,8 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out)
     all.insert(all.end(), rect.begin(), rect.end());
     all.insert(all.end(), base.begin(), base.end());
     auto tiles_of = [&](const Seg& s) {
-        if (s.kind == kSegTri) return k * (k - 1) / 2;
+        if (s.kind == kSegTri) return k * (k - 1) / 2 + (s.aug ? 2 : 0);
+        if (s.kind == kSegDiagRun) return 1;
         if (s.kind == kSegTriBase) return s.r1 * (s.r1 - 1) / 2;
         return s.mr * s.nc;
     };
@@ -161,6 +176,7 @@ bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
     for (int32_t i = 0; i < base.nseg; ++i) {
         Seg s = base.seg[i];                                // unsliced: count = blocks, t0 = 0
         s.slices = (s.kind == kSegTri || s.kind == kSegTriBase) ? sl.tri : sl.rect;
+        if (s.kind == kSegTri && s.aug && s.slices > 1) return false;   // (augmented blocks are never cut)
         segs.push_back(s);
     }
     if (sl.tail_blocks > 0 && sl.tail > 1 && !segs.empty()) {   // the end of the list, cut more finely
@@ -168,6 +184,7 @@ bool apply_slicing(const Plan& base, const Slicing& sl, Plan* out)
         std::vector<Seg> tail;
         while (want > 0 && !segs.empty()) {
             Seg& last = segs.back();
+            if (last.kind == kSegTri && last.aug) return false;
             const int32_t take = std::min(want, last.count);
             Seg cut = last;
             cut.t0 = last.t0 + last.count - take;
@@ -218,6 +235,9 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, doub
         double tiles = 0.0;
         if (it.kind == kTri) {
             tiles = 0.5 * it.nrow * (it.nrow - 1);
+        } else if (it.kind == kAug) {
+            // (writing eight tiles back takes longer than six: most of a block's fixed cost is its epilogue)
+            tiles = 8.0 + 0.6 * overhead_tiles;
         } else if (it.kind == kRect || it.kind == kRectDiag) {
             for (int r = 0; r < kRectRows; ++r)
                 for (int q = 0; q < kRectCols; ++q)
@@ -243,7 +263,8 @@ double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, doub
 }
 
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family,
-                 int32_t max_slices, double slice_overhead_tiles, double slice_per_part_tiles, bool die_groups)
+                 int32_t max_slices, double slice_overhead_tiles, double slice_per_part_tiles, bool die_groups,
+                 bool augment)
 {
     if (square) {
         // rectangles only; for small matrices the block shape with the shortest simulated makespan
@@ -323,6 +344,19 @@ bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Pla
                         *out = cand;
                     }
                     if (slicing && sh[0] == 1 && mrt == 1) try_slicings(cand);
+                    if (augment && levels == kMaxLevels) {   // the same with augmented top-level blocks
+                        tune.augment = true;
+                        if (!build_plan(T, tune, &cand) || cand.nseg < 1 || !cand.seg[0].aug) continue;
+                        // (measured: with more than two rounds of top-level blocks the finer plain plans do
+                        // as well or better; the larger blocks pay where they save a short extra round)
+                        if ((int64_t)cand.c[0] * cand.c[0] > 2 * (int64_t)ncu) continue;
+                        const double aspan = simulate_makespan(cand, ncu, overhead_tiles, slice_overhead_tiles, slice_per_part_tiles);
+                        if (aspan < best * 0.97) {
+                            best = aspan;
+                            *out = cand;
+                        }
+                        if (slicing && mrt == 1) try_slicings(cand);
+                    }
                 }
         }
     }
@@ -349,6 +383,11 @@ void plan_stats(const Plan& p, int64_t N, int64_t M, PlanStats* st)
             if (it.kind == kTri) {
                 if (head) ++r.n_tri;
                 for (int32_t u = 0; u < it.nrow; ++u) a += panel_rows(it.rows[u]);
+            } else if (it.kind == kAug) {
+                ++r.n_tri;
+                for (int32_t u = 0; u < kMaxPanels; ++u) a += panel_rows(it.rows[u]);   // (a diagonal tile's panel twice)
+                if (it.rows[4] == it.rows[0]) ++r.n_diag;
+                if (it.rows[5] == it.rows[2]) ++r.n_diag;
             } else if (it.kind == kRect || it.kind == kRectDiag) {
                 if (head) ++r.n_rect;
                 for (int32_t u = 0; u < kMaxPanels; ++u)

@@ -19,6 +19,7 @@ struct PlanTuning {
                                         // one tile row high whenever they carry the diagonal tiles
     bool xor_family = true;  // levels may use c = 2^m with the XOR family where that covers more rows
     bool die_groups = true;  // top-level blocks of the XOR family in groups of 32 that share tile rows
+    bool augment = false;    // top-level blocks take two tiles of the diagonal zones each (no recursion then)
 };
 
 // How the blocks of a plan are cut along the contraction dimension (1 = not at all): all triangle
@@ -52,7 +53,7 @@ bool build_plan(int32_t T, const PlanTuning& tune, Plan* out);
 // (storing the part; the last part to finish sums all of them).
 bool choose_plan(int32_t T, bool square, int32_t ncu, double overhead_tiles, Plan* out, bool xor_family = true,
                  int32_t max_slices = 1, double slice_overhead_tiles = 0.03, double slice_per_part_tiles = 0.0,
-                 bool die_groups = true);
+                 bool die_groups = true, bool augment = false);
 
 // Makespan, in tile units, of dispatching the plan's blocks in order onto ncu units.
 double simulate_makespan(const Plan& p, int32_t ncu, double overhead_tiles, double slice_overhead_tiles = 0.03,

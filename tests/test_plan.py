@@ -12,7 +12,7 @@ from oracle import tbs_schedule as ts
 from paper_2202_10217_amd import binding as tb
 
 B, K = 64, 4
-KIND_TRI, KIND_RECT, KIND_DIAG, KIND_EMPTY, KIND_RECTDIAG = 0, 1, 2, 3, 4
+KIND_TRI, KIND_RECT, KIND_DIAG, KIND_EMPTY, KIND_RECTDIAG, KIND_AUG = 0, 1, 2, 3, 4, 5
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -58,6 +58,20 @@ def _tiles_of(items):
         elif kind == KIND_DIAG:
             assert nrow == 1
             yield rows[0], rows[0]
+        elif kind == KIND_AUG:
+            # a triangle block on four tile rows plus two tiles, each between a row of the block and one
+            # further row: (row, column) as the codes say, row >= column (equal: the diagonal tile)
+            R, further1, further2, code1, code2 = rows[:4], rows[4], rest[7], rest[8], rest[9]
+            assert parts == 1 and nrow == 4 and all(r >= 0 for r in R) and further1 >= 0 and further2 >= 0
+            for u in range(4):
+                for v in range(u):
+                    assert R[u] > R[v]
+                    yield R[u], R[v]
+            t1 = {6: (further1, R[0]), 7: (further1, R[1])}[code1]
+            t2 = {8: (further2, R[2]), 9: (R[2], further2), 10: (further2, R[3]), 11: (R[3], further2)}[code2]
+            for r, q in (t1, t2):
+                assert r >= q
+                yield r, q
         else:
             assert kind == KIND_EMPTY
 
@@ -106,6 +120,47 @@ def test_every_pinned_tuning_covers_the_triangle_exactly_once(idx, monkeypatch):
         assert tb.tbs_syrk_lower_query(tb.TBS_F32, N, 777)["n_diag_tiles"] == T
 
 
+AUG_TUNINGS = ["10,2,3,0,1,3,1,1,0,1,1", "10,1,2,0,1,2,1,1,0,1,1", "10,2,3,0,2,3,1,1,16,4,1"]
+
+
+@pytest.mark.parametrize("family", ["", "cyclic"])
+@pytest.mark.parametrize("groups", ["0", "1"])
+@pytest.mark.parametrize("tuning", AUG_TUNINGS)
+def test_augmented_plans_cover_the_triangle_exactly_once(tuning, groups, family, monkeypatch):
+    # top-level triangle blocks that take two tiles of the diagonal zones along: every tile of the lower
+    # triangle still exactly once, for both families, with and without the groups of 32, for sizes with
+    # and without left-over tile rows and a ragged last tile; no block of a deeper level remains, and
+    # every extra tile lies in the zone of the block's row it is attached to
+    monkeypatch.setenv("TBS_PLAN_TUNING", tuning)
+    monkeypatch.setenv("TBS_SYRK_DIE_GROUPS", groups)
+    if family:
+        monkeypatch.setenv("TBS_PLAN_FAMILY", family)
+    for N in (768, 1000, 4096, 4033, 5000, 8192 + 130, 16384):
+        items = tb.tbs_syrk_lower_enumerate(tb.TBS_F64, N, 1024, 0)
+        info = tb.tbs_syrk_lower_query(tb.TBS_F64, N, 1024, 0)
+        T = (N + B - 1) // B
+        c = info["c"]
+        aug = items[items[:, 0] == KIND_AUG]
+        assert len(aug) == c * c and (items[:, 0] == KIND_TRI).sum() == 0 and info["levels"] == 1
+        assert (family == "cyclic") == (info["family"] == 0) or c & (c - 1) != 0 or info["family"] == 0
+        count = np.zeros((T, T), dtype=np.int32)
+        for r, q in _tiles_of(items):
+            assert 0 <= q <= r < T
+            count[r, q] += 1
+        assert (count[np.tril_indices(T)] == 1).all() and count.sum() == T * (T + 1) // 2
+        assert info["n_diag_tiles"] == T
+        for row in aug.tolist():
+            R, f1, f2, c1, c2 = row[3:7], row[7], row[10], row[11], row[12]
+            assert f1 // c == R[c1 - 6] // c                 # same zone as the row it is paired with
+            assert f2 // c == R[2 + (c2 - 8) // 2] // c
+        # the diagonal tiles of zones 1 and 3 are items of their own; those of zones 0 and 2 went with blocks
+        singles = sorted(items[(items[:, 0] == KIND_DIAG) & (items[:, 8] == 0)][:, 3].tolist())
+        assert singles == list(range(c, 2 * c)) + list(range(3 * c, 4 * c))
+        # A elements: six panels per block at the top level (whole tile rows)
+        if N % B == 0 or 4 * c < T:
+            assert info["A_elems_top"] == c * c * 6 * B * 1024
+
+
 @pytest.mark.parametrize("N,M", [(4096, 4096), (16384, 512), (32768, 8192), (8192, 64)])
 def test_groups_of_32_top_level_blocks_share_their_tile_rows(N, M, monkeypatch):
     # the top-level blocks of the XOR family are listed in groups of 32 that lie on 28 tile rows (a
@@ -114,6 +169,7 @@ def test_groups_of_32_top_level_blocks_share_their_tile_rows(N, M, monkeypatch):
     # consecutive blocks need many more; both orders hold the same blocks.  (By default the library groups
     # them when A is larger than the last-level cache can serve.)
     dt = tb.TBS_F32 if N == 32768 else tb.TBS_F64
+    monkeypatch.setenv("TBS_SYRK_AUGMENT", "0")             # (the paper's blocks; the eight-tile ones are tested above)
     monkeypatch.setenv("TBS_SYRK_DIE_GROUPS", "1")
     items = tb.tbs_syrk_lower_enumerate(dt, N, M, 2)
     info = tb.tbs_syrk_lower_query(dt, N, M, 2)
@@ -145,7 +201,8 @@ def test_empty_matrix():
 
 
 @pytest.mark.parametrize("N,M", [(768, 64), (4096, 4096), (4096, 32), (16384, 512), (12345, 100), (32768, 64)])
-def test_triangle_blocks_are_those_of_the_indexing_family(N, M):
+def test_triangle_blocks_are_those_of_the_indexing_family(N, M, monkeypatch):
+    monkeypatch.setenv("TBS_SYRK_AUGMENT", "0")             # the schedule of Algorithm 4 as the paper states it
     # the CPU replay of Algorithm 4 on a T x 1 problem with b = 1 lists the blocks of every level (with
     # the library's rule for the family of a level: cyclic, or XOR where a power of two covers more rows)
     T = N // B                                              # full tiles only: the replay has no ragged edge
@@ -177,9 +234,16 @@ def _is_family_block(R):
     return not all(R[u + 1] == R[u] + 1 for u in range(len(R) - 1))
 
 
-def test_query_numbers_against_the_formulas():
+def test_query_numbers_against_the_formulas(monkeypatch):
     N, M = 4096, 4096
+    # what the library runs by default at this size: eight-tile blocks (six panels each) and no blocks of
+    # their own for the diagonal zones, which loads fewer elements of A in all than the paper's blocks
+    # with the zones cut finely enough to keep every compute unit busy
+    default = tb.tbs_syrk_lower_query(tb.TBS_F64, N, M)
+    monkeypatch.setenv("TBS_SYRK_AUGMENT", "0")             # from here on: the schedule of Algorithm 4
     info = tb.tbs_syrk_lower_query(tb.TBS_F64, N, M)
+    assert default["A_elems_top"] == 16 * 16 * 6 * B * M and default["levels"] == 1
+    assert default["A_elems"] < info["A_elems"]
     S = ts.tiled_tbs_S(K, B)
     assert info["S_C_elems"] == S == 24576
     assert info["S_res_elems"] == S + 2 * K * B * 16

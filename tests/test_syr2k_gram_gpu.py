@@ -213,3 +213,24 @@ def test_larger_shapes_sampled(tb):
     den = oracle.syrk_lower_sample(np.abs(At), None, ii, jj, 1.0, 0.0)
     assert float((np.abs(got - ref) / den).max()) <= 1e-13
     assert not bool(dC[0, 1:].any()) and not bool(dC[M - 2, M - 1:].any())
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("N,M", [(96, 768), (301, 1000), (130, 2052), (64, 4033)])
+def test_gram_with_augmented_blocks_bit_exact(tb, N, M, dtype, monkeypatch):
+    # the Gram form on a plan with eight-tile blocks (column panels through the same loops); an order that
+    # is no multiple of the rows per 16-byte piece falls back to the plan without them
+    monkeypatch.setenv("TBS_PLAN_TUNING", "10,2,3,0,1,3,1,1,0,1,1")
+    code = tb.TBS_F64 if dtype == np.float64 else tb.TBS_F32
+    assert int((tb.tbs_syrk_lower_enumerate(code, M, N, 0)[:, 0] == 5).sum()) >= 9
+    A = inputs.small_int_matrix(N, M, seed=N + M, dtype=dtype)
+    C0 = inputs.symmetric_uniform(M, seed=M, dtype=dtype, int_range=(-9, 9))
+    dC = _dev(C0)
+    tb.tbs_gram_lower(_dev(A), dC, -1.0, 1.0)
+    torch.cuda.synchronize()
+    Cref = C0.astype(np.float64).copy()
+    oracle.gram_lower(A.astype(np.float64), Cref, -1.0, 1.0)
+    il, iu = np.tril_indices(M), np.triu_indices(M, 1)
+    out = dC.cpu().numpy()
+    assert np.array_equal(out[il].astype(np.float64), Cref[il])
+    assert np.array_equal(out[iu], C0[iu])

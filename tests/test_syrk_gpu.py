@@ -455,3 +455,86 @@ def test_edges_of_the_main_loop_bit_exact(tb, N, M, pad, shift, dtype):
         out = dC.cpu().numpy()
         assert np.array_equal(out[il].astype(np.float64), Cref[il])
         assert np.array_equal(out[iu], C0[iu])
+
+
+# ---- augmented triangle blocks (eight tiles: a triangle block plus two tiles of the diagonal zones) ----
+AUG_TUNING = "10,2,3,0,1,3,1,1,0,1,1"
+
+
+def _aug_blocks(tb, code, N, M):
+    items = tb.tbs_syrk_lower_enumerate(code, N, M, 0)
+    return int((items[:, 0] == 5).sum())
+
+
+@pytest.mark.parametrize("family", ["", "cyclic"])
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("N,M", [(768, 96), (1000, 301), (2051, 130), (4033, 200), (4096, 64)])
+def test_augmented_blocks_bit_exact(tb, N, M, dtype, family, monkeypatch):
+    # integer data (any order of summation gives the same bits): pins which tile every accumulator of the
+    # eight-tile blocks is written to, for both families, with whole and ragged last tile rows, a
+    # contraction length that is no multiple of the chunk, and blocks whose extra tile is a diagonal tile
+    monkeypatch.setenv("TBS_PLAN_TUNING", AUG_TUNING)
+    if family:
+        monkeypatch.setenv("TBS_PLAN_FAMILY", family)
+    code = tb.TBS_F64 if dtype == np.float64 else tb.TBS_F32
+    assert _aug_blocks(tb, code, N, M) >= 9
+    A = inputs.small_int_matrix(N, M, seed=N + M, dtype=dtype)
+    C0 = inputs.symmetric_uniform(N, seed=N, dtype=dtype, int_range=(-9, 9))
+    C0[np.triu_indices(N, 1)] = np.nan
+    il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+    for alpha, beta in ((-1.0, 1.0), (2.0, 0.0)):
+        Cg = _run(tb, A, C0, alpha, beta)
+        Cref = np.nan_to_num(C0.astype(np.float64))
+        oracle.syrk_lower(A.astype(np.float64), Cref, alpha, beta)
+        assert np.array_equal(Cg[il].astype(np.float64), Cref[il])
+        assert np.isnan(Cg[iu]).all()
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_augmented_blocks_in_tolerance_and_default_choice(tb, dtype, monkeypatch):
+    # random data against the extended-precision oracle, on the plan the library chooses by itself where
+    # that plan has augmented blocks (fp64, N = 4096, long contraction) and pinned otherwise
+    N, M = 4096, 2048
+    code = tb.TBS_F64 if dtype == np.float64 else tb.TBS_F32
+    if dtype == np.float64:
+        assert _aug_blocks(tb, code, N, M) == 256            # the default for this shape
+    else:
+        monkeypatch.setenv("TBS_SYRK_AUGMENT", "1")
+        assert _aug_blocks(tb, code, N, M) == 256
+    A = inputs.normal_matrix(N, M, seed=5, scale=1.0 / 32, dtype=dtype)
+    C0 = inputs.symmetric_uniform(N, seed=6, dtype=dtype)
+    dA, dC = _dev(A), _dev(C0)
+    ws = torch.empty(max(tb.tbs_syrk_lower_workspace(code, N, M), 16), dtype=torch.uint8, device="cuda")
+    tb.tbs_syrk_lower(dA, dC, -1.0, 1.0, workspace=ws)
+    torch.cuda.synchronize()
+    Cref, D = _reference(A, C0, -1.0, 1.0)
+    _check(dC.cpu().numpy(), C0, Cref, D, dtype)
+    monkeypatch.setenv("TBS_SYRK_AUGMENT", "0")
+    assert _aug_blocks(tb, code, N, M) == 0
+
+
+def test_augmented_plan_is_not_used_for_operands_the_fast_loop_cannot_take(tb, monkeypatch):
+    # the eight-tile blocks have no general path: with a contraction shorter than a chunk the library
+    # must fall back to the plan without them (same result, bit for bit on integer data)
+    monkeypatch.setenv("TBS_PLAN_TUNING", AUG_TUNING)
+    N, M = 1000, 9
+    A = inputs.small_int_matrix(N, M, seed=1)
+    C0 = inputs.symmetric_uniform(N, seed=2, int_range=(-9, 9))
+    Cg = _run(tb, A, C0, -1.0, 1.0)
+    Cref = C0.copy()
+    oracle.syrk_lower(A, Cref, -1.0, 1.0)
+    il = np.tril_indices(N)
+    assert np.array_equal(Cg[il], Cref[il])
+    # odd leading dimension and an offset pointer are fine for the fast loop: the augmented plan runs
+    M = 100
+    assert _aug_blocks(tb, tb.TBS_F64, N, M) >= 9
+    A = inputs.small_int_matrix(N, M, seed=3)
+    buf = torch.zeros(N * (M + 3) + 8, dtype=torch.float64, device="cuda")
+    Av = buf[1:1 + N * (M + 3)].view(N, M + 3)[:, :M]
+    Av.copy_(_dev(A))
+    dC = _dev(C0)
+    tb.tbs_syrk_lower(Av, dC, 1.0, -1.0)
+    torch.cuda.synchronize()
+    Cref = C0.copy()
+    oracle.syrk_lower(A, Cref, 1.0, -1.0)
+    assert np.array_equal(dC.cpu().numpy()[il], Cref[il])
