@@ -43,6 +43,8 @@ def build(verbose: bool = False, incremental: bool = False) -> str:
     syrk = os.path.join(CSRC, "syrk_kernels.hip")
     units = [("syrk_f64", syrk, ["-DTBS_UNIT_SYRK", "-DTBS_UNIT_TYPE=double"]),
              ("syrk_f32", syrk, ["-DTBS_UNIT_SYRK", "-DTBS_UNIT_TYPE=float"]),
+             ("syrk_aug_f64", syrk, ["-DTBS_UNIT_SYRK_AUG", "-DTBS_UNIT_TYPE=double"]),
+             ("syrk_aug_f32", syrk, ["-DTBS_UNIT_SYRK_AUG", "-DTBS_UNIT_TYPE=float"]),
              ("syr2k_f64", syrk, ["-DTBS_UNIT_SYR2K", "-DTBS_UNIT_TYPE=double"]),
              ("syr2k_f32", syrk, ["-DTBS_UNIT_SYR2K", "-DTBS_UNIT_TYPE=float"]),
              ("gemm_f64", syrk, ["-DTBS_UNIT_GEMM", "-DTBS_UNIT_TYPE=double"]),

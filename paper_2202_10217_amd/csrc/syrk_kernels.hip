@@ -660,7 +660,42 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
 
     // Epilogue.
     const int col16 = w * 16 + (lane & 15);
-    if (FAST && !ragged && (int64_t)kTile * m.ldc * (int64_t)sizeof(T) < ((int64_t)1 << 32)) {
+    bool any_may_be_diagonal = false;
+#pragma unroll
+    for (int sl = 0; sl < Shape::NSLOT; ++sl)
+        if (((SLOTS >> sl) & 1u) && Shape::may_be_diagonal(sl)) any_may_be_diagonal = true;
+    // (eight tiles in fp64 take every accumulator register, the compiler has no room to spare there: only
+    // the second form below, which needs fewer address registers)
+    constexpr bool kNoSpareRegisters = sizeof(T) == 8 && __builtin_popcount(SLOTS) > 6;
+    if (FAST && !ragged && !kNoSpareRegisters && (!any_may_be_diagonal || dmask == 0)) {
+        // no diagonal tile in the block: the old values of three tiles are requested at once (the operand
+        // registers of the loop are free now), then their strips are computed and stored
+        const bool rd = m.beta != T(0);
+#pragma unroll
+        for (int s0 = 0; s0 < Shape::NSLOT; s0 += 3) {      // three tiles' old values in flight at a time
+            TileStrip<T> old[3];
+#pragma unroll
+            for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+                for (int j = 0; j < Shape::NB; ++j) {
+                    const int sl = Shape::slot(i, j);
+                    if (slot_on<Shape>(SLOTS, i, j) && sl >= s0 && sl < s0 + 3 && rd)
+                        old[sl - s0].template load<false>(m, prow[Shape::a_panel(i)] * kTile,
+                                                          prow[Shape::b_panel(j)] * kTile + col16, lane, false);
+                }
+#pragma unroll
+            for (int i = 0; i < Shape::NA; ++i)
+#pragma unroll
+                for (int j = 0; j < Shape::NB; ++j) {
+                    const int sl = Shape::slot(i, j);
+                    if (slot_on<Shape>(SLOTS, i, j) && sl >= s0 && sl < s0 + 3)
+                        store_strip<T, false>(m, prow[Shape::a_panel(i)] * kTile,
+                                              prow[Shape::b_panel(j)] * kTile + col16, lane, acc[sl], old[sl - s0],
+                                              false);
+                }
+        }
+    } else if (FAST && !ragged && (int64_t)kTile * m.ldc * (int64_t)sizeof(T) < ((int64_t)1 << 32)) {
+        // blocks with diagonal tiles (rectangles of triangular regions, some augmented triangle blocks)
         // the old values of EG tiles are requested at once (the operand registers of the loop are free
         // now), then their strips are computed and stored.  Tiles are taken in the order of their slots;
         // EG is what fits the registers: all tiles in fp32 (at most 128 registers of values), up to four
@@ -688,7 +723,15 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
                     }
             // every old value has arrived before the first (predicated) store: s_waitcnt vmcnt(0), told to
             // the compiler so that it places no waits of its own between the stores
-            if (rd) __builtin_amdgcn_s_waitcnt(0x0F70);
+            // (only where a tile of the group may be diagonal: otherwise the compiler's own waits let the
+            // first tile's arithmetic and stores start while the later tiles' values are still arriving)
+            bool any_diag = false;
+#pragma unroll
+            for (int sl = 0; sl < Shape::NSLOT; ++sl) {
+                const int d = __builtin_popcount(SLOTS & ((1u << sl) - 1u));
+                if (((SLOTS >> sl) & 1u) && d >= t0 && d < t0 + EG && Shape::may_be_diagonal(sl)) any_diag = true;
+            }
+            if (rd && any_diag) __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
             for (int i = 0; i < Shape::NA; ++i)
 #pragma unroll
@@ -844,7 +887,11 @@ struct SliceSpace {
     int* flag = nullptr;            // one int of LDS
 };
 
-template <typename T, bool TRI = true, class MatsT>
+// What a kernel's plans contain besides rectangular blocks: nothing (SYR2K), triangle blocks (Algorithm 4),
+// or augmented triangle blocks.
+constexpr int kBlocksRect = 0, kBlocksTri = 1, kBlocksAug = 2;
+
+template <typename T, int KINDS, class MatsT>
 __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const MatsT& m0, T* lds,
                                          const SliceSpace<T>& sp)
 {
@@ -877,16 +924,18 @@ __device__ __forceinline__ void run_item(const Plan& plan, int32_t id, const Mat
         x.kind = kRectDiag;
     }
     if (x.kind == kTri) {
-        if constexpr (TRI) run_block<T, TriShape>(x, m, lds, sc);       // (plans of rectangles have none)
+        if constexpr (KINDS == kBlocksTri) run_block<T, TriShape>(x, m, lds, sc);
     } else if (x.kind == kAug) {
         // (the host hands out augmented plans only for operands that suit the assembly loops)
-        if constexpr (TRI) run_aug_block<T>(x, m, lds);
+        if constexpr (KINDS == kBlocksAug) run_aug_block<T>(x, m, lds);
     } else if (x.kind == kRect || x.kind == kRectDiag) {
         run_block<T, RectShape>(x, m, lds, sc, x.kind == kRectDiag);
     }
 }
 
-// The SYRK kernel.  NPASS, TRI: 1, true for SYRK and the Gram form; 2, false for SYR2K (rectangles only).
+// The SYRK kernel.  NPASS: 1 for SYRK and the Gram form, 2 for SYR2K.  KINDS: which blocks besides
+// rectangles its plans have (see kBlocksRect ..): there is one kernel per kind, because the code of all
+// block shapes in one kernel leaves the compiler too few registers outside the assembly loops.
 //
 // ctr == nullptr: one workgroup per block of the plan (used when the plan has no more blocks than the
 // launch may have workgroups): workgroup b runs item b.
@@ -919,7 +968,7 @@ __device__ __forceinline__ int die_of_this_workgroup()
     return (int)(id % kTeams);
 }
 
-template <typename T, int NPASS, bool TRI>
+template <typename T, int NPASS, int KINDS>
 __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, NPASS> m, unsigned int* ctr, T* ws,
                                                             unsigned int* slice_ctr)
 {
@@ -977,7 +1026,7 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, N
             }
         }
         if (id < 0) break;
-        run_item<T, TRI>(plan, id, m, reinterpret_cast<T*>(smem), sp);
+        run_item<T, KINDS>(plan, id, m, reinterpret_cast<T*>(smem), sp);
     }
     if (persistent && threadIdx.x == 0) {
         __threadfence();
@@ -1023,7 +1072,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt_kernel(int m_rows, int n_col
 // plans with cut blocks.  Its event, if any, is attached to the kernel: it completes with the launch.
 // NPASS = 1: C <- beta C + alpha A A^T (b unused); NPASS = 2: C <- beta C + alpha (A B^T + B A^T), plan
 // of rectangles only.
-template <typename T, int NPASS>
+template <typename T, int NPASS, int KINDS>
 hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
                          const OperandDesc& b, double beta, void* C, int64_t ldc, int max_workgroups, void* ws,
                          const CounterLease& lease, hipStream_t stream)
@@ -1033,7 +1082,6 @@ hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, c
     const bool persistent = max_workgroups > 0 && plan.n_items > max_workgroups;
     if ((persistent && lease.ctr == nullptr) || (plan.n_ws_blocks > 0 && lease.slice_ctr == nullptr))
         return hipErrorInvalidValue;
-    constexpr bool TRI = NPASS == 1;
     Mats<T, NPASS> m;
     const Side<T> sa = {(const T*)a.p, a.rs, a.ks}, sb = {(const T*)b.p, b.rs, b.ks};
     m.R[0] = sa;
@@ -1050,7 +1098,7 @@ hipError_t launch_syrk_t(const Plan& plan, int64_t N, int64_t M, double alpha, c
     m.beta = (T)beta;
     m.lower = true;
     // (one kernel for both forms: without counters, workgroup b runs item b)
-    hipExtLaunchKernelGGL((tbs_syrk_kernel<T, NPASS, TRI>), dim3((unsigned)(persistent ? max_workgroups : plan.n_items)),
+    hipExtLaunchKernelGGL((tbs_syrk_kernel<T, NPASS, KINDS>), dim3((unsigned)(persistent ? max_workgroups : plan.n_items)),
                           dim3(kThreads), 0, stream, nullptr, lease.done, 0, plan, m,
                           persistent ? lease.ctr : (unsigned int*)nullptr, (T*)ws, lease.slice_ctr);
     return hipGetLastError();
@@ -1090,7 +1138,7 @@ hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const vo
 
 // ---- translation units ---------------------------------------------------------------------------
 // The file is compiled several times in parallel (each kernel template with its many instances takes
-// minutes): -DTBS_UNIT_SYRK or -DTBS_UNIT_GEMM with -DTBS_UNIT_TYPE=double|float instantiates one
+// minutes): -DTBS_UNIT_SYRK, -DTBS_UNIT_SYRK_AUG, -DTBS_UNIT_SYR2K or -DTBS_UNIT_GEMM with -DTBS_UNIT_TYPE=double|float instantiates one
 // launcher (and the kernels it launches), -DTBS_UNIT_DISPATCH defines the entry points that choose
 // between them; without any of these macros one translation unit holds everything.
 #define TBS_LAUNCH_SYRK_ARGS \
@@ -1100,17 +1148,21 @@ hipError_t launch_gemm_t(int64_t m, int64_t n, int64_t K, double alpha, const vo
     int64_t, int64_t, int64_t, double, const void*, int64_t, const void*, int64_t, double, void*, int64_t, int, \
         hipStream_t
 #if defined(TBS_UNIT_SYRK)
-template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 1>(TBS_LAUNCH_SYRK_ARGS);
+template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 1, kBlocksTri>(TBS_LAUNCH_SYRK_ARGS);
+#elif defined(TBS_UNIT_SYRK_AUG)
+template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 1, kBlocksAug>(TBS_LAUNCH_SYRK_ARGS);
 #elif defined(TBS_UNIT_SYR2K)
-template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 2>(TBS_LAUNCH_SYRK_ARGS);
+template hipError_t launch_syrk_t<TBS_UNIT_TYPE, 2, kBlocksRect>(TBS_LAUNCH_SYRK_ARGS);
 #elif defined(TBS_UNIT_GEMM)
 template hipError_t launch_gemm_t<TBS_UNIT_TYPE>(TBS_LAUNCH_GEMM_ARGS);
 #else
 #if defined(TBS_UNIT_DISPATCH)
-extern template hipError_t launch_syrk_t<double, 1>(TBS_LAUNCH_SYRK_ARGS);
-extern template hipError_t launch_syrk_t<float, 1>(TBS_LAUNCH_SYRK_ARGS);
-extern template hipError_t launch_syrk_t<double, 2>(TBS_LAUNCH_SYRK_ARGS);
-extern template hipError_t launch_syrk_t<float, 2>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<double, 1, kBlocksTri>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<float, 1, kBlocksTri>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<double, 1, kBlocksAug>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<float, 1, kBlocksAug>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<double, 2, kBlocksRect>(TBS_LAUNCH_SYRK_ARGS);
+extern template hipError_t launch_syrk_t<float, 2, kBlocksRect>(TBS_LAUNCH_SYRK_ARGS);
 extern template hipError_t launch_gemm_t<double>(TBS_LAUNCH_GEMM_ARGS);
 extern template hipError_t launch_gemm_t<float>(TBS_LAUNCH_GEMM_ARGS);
 #endif
@@ -1205,10 +1257,20 @@ hipError_t launch_syrk(bool f32, const Plan& plan, int64_t N, int64_t M, double 
                        double beta, void* C, int64_t ldc, int max_workgroups, void* workspace,
                        const CounterLease& lease, hipStream_t stream)
 {
-    return f32 ? launch_syrk_t<float, 1>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups, workspace, lease,
-                                         stream)
-               : launch_syrk_t<double, 1>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups, workspace, lease,
-                                          stream);
+    bool aug = false;
+    for (int32_t sg = 0; sg < plan.nseg; ++sg) aug = aug || (plan.seg[sg].kind == kSegTri && plan.seg[sg].aug);
+    for (int32_t sg = 0; sg < plan.nseg && aug; ++sg)       // (such plans have no other triangle blocks)
+        if ((plan.seg[sg].kind == kSegTri && !plan.seg[sg].aug) || plan.seg[sg].kind == kSegTriBase)
+            return hipErrorInvalidValue;
+    if (aug)
+        return f32 ? launch_syrk_t<float, 1, kBlocksAug>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups,
+                                                         workspace, lease, stream)
+                   : launch_syrk_t<double, 1, kBlocksAug>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups,
+                                                          workspace, lease, stream);
+    return f32 ? launch_syrk_t<float, 1, kBlocksTri>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups, workspace,
+                                                     lease, stream)
+               : launch_syrk_t<double, 1, kBlocksTri>(plan, N, M, alpha, a, a, beta, C, ldc, max_workgroups, workspace,
+                                                      lease, stream);
 }
 
 hipError_t launch_syr2k(bool f32, const Plan& plan, int64_t N, int64_t M, double alpha, const OperandDesc& a,
@@ -1218,10 +1280,10 @@ hipError_t launch_syr2k(bool f32, const Plan& plan, int64_t N, int64_t M, double
     if (plan.n_ws_blocks > 0) return hipErrorInvalidValue;
     for (int32_t sg = 0; sg < plan.nseg; ++sg)
         if (plan.seg[sg].kind == kSegTri || plan.seg[sg].kind == kSegTriBase) return hipErrorInvalidValue;
-    return f32 ? launch_syrk_t<float, 2>(plan, N, M, alpha, a, b, beta, C, ldc, max_workgroups, nullptr, lease,
-                                         stream)
-               : launch_syrk_t<double, 2>(plan, N, M, alpha, a, b, beta, C, ldc, max_workgroups, nullptr, lease,
-                                          stream);
+    return f32 ? launch_syrk_t<float, 2, kBlocksRect>(plan, N, M, alpha, a, b, beta, C, ldc, max_workgroups, nullptr,
+                                                      lease, stream)
+               : launch_syrk_t<double, 2, kBlocksRect>(plan, N, M, alpha, a, b, beta, C, ldc, max_workgroups, nullptr,
+                                                       lease, stream);
 }
 
 size_t syrk_workspace_bytes(bool f32, const Plan& plan)
