@@ -122,8 +122,10 @@ tbs_status tbs_gram_lower(tbs_dtype dtype, int64_t N, int64_t M, double alpha,
 
 /* ------------------------------------------------------------------------------------------------
  * tbs_syrk_lower for callers that cannot allocate device memory: code under HIP graph capture, tight
- * serving loops, harnesses that forbid hipMalloc.  Same operation, arguments, plan and results (bit
- * for bit) as tbs_syrk_lower called with the workspace that tbs_syrk_lower_workspace() asks for, but
+ * serving loops, harnesses that forbid hipMalloc.  Same operation and arguments as tbs_syrk_lower called
+ * with the workspace that tbs_syrk_lower_workspace() asks for, and the same plan and results bit for bit
+ * wherever that plan has no eight-tile blocks (TBS_SYRK_AUGMENT=0 in the environment makes that so at
+ * every size; this entry point never uses them, the results then agree within rounding), but
  * the scratch memory (the parts of blocks computed in parts, and the counters of the launch) is an
  * array at file scope in the library's device code: TBS_NOALLOC_SCRATCH_BYTES of device memory that
  * every GPU the library runs on holds from the moment the library is loaded until the process ends.
@@ -161,7 +163,7 @@ typedef struct {
                                /* and f(0)=j, f(1)=i, f(2)=i^j, f(3)=i^(x j mod x^m+x+1)            */
     int32_t max_slices;        /* blocks are cut along the contraction dimension into at most this many parts */
     int64_t n_items;           /* workgroups launched                                            */
-    int64_t n_tri_blocks;      /* triangle blocks, all levels                                    */
+    int64_t n_tri_blocks;      /* triangle blocks, all levels (six tiles, or eight: see _enumerate) */
     int64_t n_rect_blocks;     /* rectangular blocks (leftover rows, recursion base)             */
     int64_t n_diag_tiles;      /* diagonal tiles                                                 */
     int64_t S_C_elems;         /* b^2 k(k-1)/2: C elements resident per triangle block           */

@@ -563,7 +563,9 @@ tbs_status tbs_syrk_lower_noalloc(tbs_dtype dtype, int64_t N, int64_t M, double 
     if (st != TBS_OK) return st;
     if (N == 0) return TBS_OK;
     const int32_t T = (int32_t)((N + kTile - 1) / kTile);
-    const tbs::Plan* plan = cached_plan(T, false, dtype, M, true);
+    // (the plan without eight-tile blocks: their fp64 kernel spills a few registers to memory that the
+    // runtime provides per queue when such a kernel is first launched, which this entry point must not cause)
+    const tbs::Plan* plan = cached_plan(T, false, dtype, M, true, false);
     if (!plan) return TBS_EINVAL;
     if (tbs::syrk_workspace_bytes(dtype == TBS_F32, *plan) > tbs::kStaticWorkspaceBytes) return TBS_EWORKSPACE;
     unsigned char* base = nullptr;
