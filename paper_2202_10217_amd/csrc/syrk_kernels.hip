@@ -417,10 +417,39 @@ __device__ __forceinline__ void store_strip_fast(T* strip, const StripOffsets<T>
 // ---- blocks cut along the contraction dimension -------------------------------------------------
 // A sliced block is computed by `slices` workgroups, each over its share of the columns of A.  Every
 // one writes its accumulators to its own place in the workspace (in register order: coalesced, no
-// layout change), then adds one to the block's counter; the workgroup that finds the counter at
+// layout change; device-scope stores, see part_store), then adds one to the block's counter; the workgroup that finds the counter at
 // slices - 1 is the last: it reads all parts back, adds them in the order of the slices (so the
 // result does not depend on who finished when), and runs the ordinary epilogue on the sum.  No
 // workgroup ever waits for another.  part == nullptr: an ordinary, whole block.
+// Device-scope accesses to the parts of cut blocks.  The dies of the chip have an L2 each, which are not
+// coherent with one another for ordinary loads and stores; a `__threadfence()` makes a workgroup's stores
+// visible to the others by writing back every dirty line of its die's L2 and invalidating that L2
+// (`buffer_wbl2 sc1` + `buffer_inv sc1`): tens of microseconds per fence next to running blocks whose
+// panels the invalidation throws out.  Relaxed atomic stores and loads at device scope instead go through
+// to the memory side line by line and need no fence: a part is complete at device scope when its stores have
+// been acknowledged (`s_waitcnt vmcnt(0)`), and the counter, a device-scope atomic as well, is bumped after
+// that; whoever reads the parts does so after its own bump has returned the full count.
+__device__ __forceinline__ void part_store(double* p, double v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), (unsigned long long)__double_as_longlong(v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void part_store(float* p, float v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned int*>(p), __float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double part_load(const double* p)
+{
+    return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ float part_load(const float* p)
+{
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned int*>(p), __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT));
+}
+
 template <typename T>
 struct SliceCtx {
     T* part = nullptr;              // this block's stretch of the workspace: [slices][NSLOT][16][256]
@@ -618,14 +647,15 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) dst[(rb * 4 + g) * kThreads] = acc[s][rb][g];
+                    for (int g = 0; g < 4; ++g) part_store(&dst[(rb * 4 + g) * kThreads], acc[s][rb][g]);
             }
-        __threadfence();                                    // the part is visible device-wide ...
-        __syncthreads();
-        if (tid == 0) *sc.flag = (atomicAdd(sc.ctr, 1u) == (unsigned)(sc.slices - 1)) ? 1 : 0;   // ... before the count
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this thread's share of the part is out ...
+        __syncthreads();                                    // ... and everybody's ...
+        if (tid == 0)                                       // ... before the count
+            *sc.flag = (__hip_atomic_fetch_add(sc.ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                        (unsigned)(sc.slices - 1)) ? 1 : 0;
         __syncthreads();
         if (*sc.flag == 0) return;                          // not the last part of this block
-        __threadfence();
         T zero = T(0);
         asm volatile("" : "+v"(zero));                      // (as above: no vector of zeros kept for the whole kernel)
 #pragma unroll
@@ -643,7 +673,7 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
                         const int sl = min(sl0 + d, sc.slices - 1);
                         const T* src = sc.part + ((size_t)(sl * NS + s) * 16) * kThreads + tid;
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) v[d][e] = src[e * kThreads];
+                        for (int e = 0; e < 16; ++e) v[d][e] = part_load(&src[e * kThreads]);
                     }
 #pragma unroll
                     for (int d = 0; d < 2; ++d)
@@ -655,7 +685,8 @@ __device__ __forceinline__ void block_body(const MatsT& m, const int (&prow)[Sha
                         }
                 }
             }
-        if (tid == 0) *sc.ctr = 0u;                         // for the next launch that uses this counter
+        if (tid == 0)                                       // for the next launch that uses this counter
+            __hip_atomic_store(sc.ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // Epilogue.
@@ -1029,11 +1060,12 @@ __global__ __launch_bounds__(kThreads) void tbs_syrk_kernel(Plan plan, Mats<T, N
         run_item<T, KINDS>(plan, id, m, reinterpret_cast<T*>(smem), sp);
     }
     if (persistent && threadIdx.x == 0) {
-        __threadfence();
+        // (no fence: the counters are only ever touched by device-scope atomics; this one follows the
+        // return of the workgroup's last fetch from the list, and the reset follows the return of this one)
         if (atomicAdd(&ctr[1], 1u) == gridDim.x - 1) {  // every workgroup has left its loop
 #pragma unroll
-            for (int c = 0; c < kLaunchCounters; ++c) ctr[c] = 0u;
-            __threadfence();
+            for (int c = 0; c < kLaunchCounters; ++c)
+                __hip_atomic_store(&ctr[c], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
