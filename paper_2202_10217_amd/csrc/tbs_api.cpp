@@ -109,11 +109,10 @@ const tbs::Plan* cached_plan(int32_t T, bool square, tbs_dtype dtype, int64_t M,
         // Top-level triangle blocks that take two tiles of the diagonal zones with them (eight tiles per
         // block instead of six: the fixed cost of a block is spread over a third more work, and the zones
         // need no blocks of their own).  TBS_SYRK_AUGMENT=1 / 0 lets the planner consider them or not.
-        // By default in fp64 with tiles that take at least 2.5 times a block's fixed cost (M of about 2000
-        // and more), and there only where a compute unit gets at most two top-level blocks (the planner's
-        // rule): measured +1.4 to +4 % for N = 4096 .. 5632; with shorter tiles or in fp32 the larger
-        // epilogue eats the gain (-4 to +1 %).
-        bool augment = kAugmentByDefault && dtype == TBS_F64 && block_us <= 0.4 * tile_us;
+        // By default in fp64, and there only where a compute unit gets at most two top-level blocks (the
+        // planner's rule): measured +0.5 to +4.9 % for N = 4096 .. 5632, M = 1024 .. 16384; in fp32 the larger
+        // epilogue eats the gain (-1.4 to +5.5 %, most sizes slightly negative).
+        bool augment = kAugmentByDefault && dtype == TBS_F64;
         if (!env.augment.empty()) augment = env.augment[0] != '0';
         // (the smallest M of the bucket must give the assembly loops a whole chunk)
         if (!allow_aug || ((int64_t)3 << bucket) / 4 < (dtype == TBS_F32 ? 32 : 16)) augment = false;
