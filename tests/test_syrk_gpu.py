@@ -538,3 +538,33 @@ def test_augmented_plan_is_not_used_for_operands_the_fast_loop_cannot_take(tb, m
     Cref = C0.copy()
     oracle.syrk_lower(A, Cref, 1.0, -1.0)
     assert np.array_equal(dC.cpu().numpy()[il], Cref[il])
+
+
+def test_cut_blocks_on_several_streams_at_once(tb):
+    # plans with blocks cut along the contraction dimension on three streams at the same time, each call
+    # with a workspace of its own: the parts travel through device-scope stores and loads and a counter per
+    # block, the three launches use different sets of counters; integer data, so a part that is read before
+    # it has arrived, or added twice, shows as a wrong integer
+    shapes = [(2048, 2080), (4096, 1024), (1100, 3000)]
+    streams = [torch.cuda.Stream() for _ in shapes]
+    dAs, dCs, wss, refs = [], [], [], []
+    for i, (N, M) in enumerate(shapes):
+        assert tb.tbs_syrk_lower_query(tb.TBS_F64, N, M)["n_sliced_blocks"] > 0
+        A = inputs.small_int_matrix(N, M, seed=60 + i)
+        C0 = inputs.symmetric_uniform(N, seed=70 + i, int_range=(-3, 3))
+        R = C0.copy()
+        for _ in range(4):
+            oracle.syrk_lower(A, R, -1.0, 1.0)
+        refs.append(R)
+        dAs.append(_dev(A))
+        dCs.append(_dev(C0))
+        wss.append(torch.empty(tb.tbs_syrk_lower_workspace(tb.TBS_F64, N, M), dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for i in range(len(shapes)):
+            with torch.cuda.stream(streams[i]):
+                tb.tbs_syrk_lower(dAs[i], dCs[i], -1.0, 1.0, workspace=wss[i])
+    torch.cuda.synchronize()
+    for i, (N, M) in enumerate(shapes):
+        il = np.tril_indices(N)
+        assert np.array_equal(dCs[i].cpu().numpy()[il], refs[i][il]), shapes[i]
