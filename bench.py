@@ -255,7 +255,9 @@ def main():
         es = 8 if w.dname == "f64" else 4
         traffic, source = profile_traffic(args.workload, args.square)
         out["config"] = {"workload": args.workload, "N": w.N, "M": w.M, "alpha": w.alpha, "beta": w.beta,
-                         "schedule": "square-blocks" if args.square else "triangle-blocks",
+                         "schedule": "square-blocks" if args.square else
+                                     ("triangle-blocks-of-eight-tiles" if info["S_C_elems"] == 8 * 64 * 64
+                                      else "triangle-blocks"),
                          "k": info["k"], "b": info["b"], "c": info["c"], "l": info["l"],
                          "workgroups": info["n_items"]}
         out["roofline"] = {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "peak_source": "published",

@@ -166,7 +166,7 @@ typedef struct {
     int64_t n_tri_blocks;      /* triangle blocks, all levels (six tiles, or eight: see _enumerate) */
     int64_t n_rect_blocks;     /* rectangular blocks (leftover rows, recursion base)             */
     int64_t n_diag_tiles;      /* diagonal tiles                                                 */
-    int64_t S_C_elems;         /* b^2 k(k-1)/2: C elements resident per triangle block           */
+    int64_t S_C_elems;         /* C elements resident per block: b^2 k(k-1)/2, 8 b^2 for eight-tile blocks */
     int64_t S_res_elems;       /* S_C plus the LDS staging buffers of A                          */
     double  A_elems;           /* A elements this plan loads (all blocks, all levels)            */
     double  A_elems_top;       /* of which top-level triangle blocks: Q1 = c^2 k b M             */

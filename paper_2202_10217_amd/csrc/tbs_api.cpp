@@ -687,9 +687,13 @@ tbs_status tbs_syrk_lower_query(tbs_dtype dtype, int64_t N, int64_t M, int32_t s
     r.n_tri_blocks = st.n_tri;
     r.n_rect_blocks = st.n_rect;
     r.n_diag_tiles = st.n_diag;
-    r.S_C_elems = (int64_t)kTile * kTile * kK * (kK - 1) / 2;
+    // (a plan with eight-tile blocks keeps eight tiles of C per block and stages six panels: the bound it is
+    // held against is the one for that larger fast memory)
+    bool eight = false;
+    for (int32_t sg = 0; sg < plan->nseg; ++sg) eight = eight || (plan->seg[sg].kind == tbs::kSegTri && plan->seg[sg].aug);
+    r.S_C_elems = (int64_t)kTile * kTile * (eight ? 8 : kK * (kK - 1) / 2);
     const int64_t kc = dtype == TBS_F32 ? 32 : 16;      // staged columns per chunk, two buffers
-    r.S_res_elems = r.S_C_elems + 2 * (int64_t)kK * kTile * kc;
+    r.S_res_elems = r.S_C_elems + 2 * (int64_t)(eight ? kK + 2 : kK) * kTile * kc;
     r.A_elems = st.A_elems;
     r.A_elems_top = st.A_elems_top;
     r.C_elems = st.C_elems;

@@ -243,6 +243,10 @@ def test_query_numbers_against_the_formulas(monkeypatch):
     monkeypatch.setenv("TBS_SYRK_AUGMENT", "0")             # from here on: the schedule of Algorithm 4
     info = tb.tbs_syrk_lower_query(tb.TBS_F64, N, M)
     assert default["A_elems_top"] == 16 * 16 * 6 * B * M and default["levels"] == 1
+    # ... and is held against the bound for the larger fast memory it uses (eight tiles of C per block)
+    assert default["S_C_elems"] == 8 * B * B and default["S_res_elems"] == 8 * B * B + 2 * 6 * B * 16
+    assert math.isclose(default["tbs_bound_elems"], ts.syrk_lower_bound(N, M, 8 * B * B), rel_tol=1e-12)
+    assert default["A_elems"] >= default["tbs_bound_elems"]
     assert default["A_elems"] < info["A_elems"]
     S = ts.tiled_tbs_S(K, B)
     assert info["S_C_elems"] == S == 24576
