@@ -568,3 +568,23 @@ def test_cut_blocks_on_several_streams_at_once(tb):
     for i, (N, M) in enumerate(shapes):
         il = np.tril_indices(N)
         assert np.array_equal(dCs[i].cpu().numpy()[il], refs[i][il]), shapes[i]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_augmented_blocks_with_die_groups_bit_exact(tb, dtype, monkeypatch):
+    # the eight-tile blocks handed out in groups of 32 per die (both options forced on; persistent launch:
+    # 256 top-level blocks and the left-over tiles on fewer workgroups than blocks)
+    monkeypatch.setenv("TBS_PLAN_TUNING", AUG_TUNING)
+    monkeypatch.setenv("TBS_SYRK_DIE_GROUPS", "1")
+    monkeypatch.setenv("TBS_SYRK_RESERVE", "64")
+    N, M = 4096, 96
+    code = tb.TBS_F64 if dtype == np.float64 else tb.TBS_F32
+    assert _aug_blocks(tb, code, N, M) == 256
+    A = inputs.small_int_matrix(N, M, seed=11, dtype=dtype)
+    C0 = inputs.symmetric_uniform(N, seed=12, dtype=dtype, int_range=(-9, 9))
+    Cg = _run(tb, A, C0, -1.0, 1.0)
+    Cref = C0.astype(np.float64).copy()
+    oracle.syrk_lower(A.astype(np.float64), Cref, -1.0, 1.0)
+    il, iu = np.tril_indices(N), np.triu_indices(N, 1)
+    assert np.array_equal(Cg[il].astype(np.float64), Cref[il])
+    assert np.array_equal(Cg[iu], C0[iu])
